@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged decode-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+
+A step is one pass of the whole hot path over one batch of synthetic input
+resident in HBM: every decode-attention call of the workload, then the merge
+of the partials.  The default workload is the GQA batch-256 decode step
+(32 q / 8 kv heads, head_dim 128, bf16, lognormal contexts, split-KV chunks of
+1024 tokens, merge).  One JSON line is printed.
+
+  value      KV bytes the step must read / step time  (GB/s), whole job
+  roofline   the decode-attention kernel alone: algorithmic bytes per launch /
+             its mean duration measured with events on the launch stream,
+             against the 8 TB/s HBM peak
+  cpu_baseline  the CPU fp64 oracle timed on this host on the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per decode-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/), scaled by the factor the same counters show for the plain copy kernel; None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(w) -> int:
+    """Bytes one pass of the decode-attention calls must move: the KV of every attended token,
+    its share of the block table (4 bytes per 16-token page), q, and the partial rows written."""
+    total = w.kv_bytes()
+    for c in w.calls:
+        tok = np.maximum(c.ctx_end.astype(np.int64) - c.ctx_begin, 0)
+        total += int(((tok + w.block_size - 1) // w.block_size).sum()) * 4
+        total += w.batch * w.num_q_heads * w.head_dim * w.elem_bytes
+        if c.chunk_tokens:
+            n_part = int(((tok + c.chunk_tokens - 1) // c.chunk_tokens).sum())
+        else:
+            n_part = int((tok > 0).sum())
+        total += n_part * w.num_q_heads * (w.head_dim + 1) * 4
+    return total
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--pools", type=int, default=2, help="physical KV pool copies rotated between steps")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector, 2 matrix-core")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2603_12831_amd import binding, workloads as wl
+    from paper_2603_12831_amd.runner import DeviceWorkload
+
+    if not torch.cuda.is_available():
+        print("no GPU visible; the benchmark has no CPU path", file=sys.stderr)
+        return 2
+    binding.load_library()
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+
+    w = wl.MAKERS[args.workload](workers=cores)
+    dw = DeviceWorkload(w, n_pool_copies=max(1, args.pools))
+    kv_bytes = w.kv_bytes()
+    alg_bytes = algorithmic_bytes(w)
+
+    for i in range(args.warmup):
+        dw.run(kernel=args.kernel, pool=i % args.pools)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        dw.run_attention(kernel=args.kernel, pool=i % args.pools)
+        ev[i][1].record()
+        dw.run_merge()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    step_ms = (t1 - t0) * 1e3 / args.steps
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) / len(w.calls)
+    attn_ms_min = float(np.min([a.elapsed_time(b) for a, b in ev])) / len(w.calls)
+
+    achieved = alg_bytes / len(w.calls) / (attn_ms * 1e-3) / 1e9
+    out = {
+        "metric": "decode-attention KV GB/s (paged decode attention + partial merge, whole step)",
+        "value": kv_bytes / (step_ms * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 inputs, f32 accumulate" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "page_tokens": w.block_size,
+                   "context_tokens_total": int(w.ctx_len.astype(np.int64).sum()),
+                   "chunk_tokens": w.calls[0].chunk_tokens, "kv_bytes_per_step": kv_bytes,
+                   "pool_copies_rotated": args.pools},
+        "pct_hbm_peak": 100.0 * kv_bytes / (step_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "merged_tokens_per_s": w.batch / (step_ms * 1e-3),
+        "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                     "kernel": "decode attention", "algorithmic_bytes_per_launch": alg_bytes // len(w.calls)},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        # bounded sample: as many whole sequences (every head, full context) as fit ~2 GB of KV
+        per_seq = w.ctx_len.astype(np.int64) * 2 * w.num_kv_heads * w.head_dim * w.elem_bytes
+        n_seq = int(min(w.batch, max(1, np.searchsorted(np.cumsum(per_seq), 2.2e9) + 1)))
+        seqs = np.arange(n_seq)
+        c0 = time.perf_counter()
+        oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, None, w.ctx_len, w.sm_scale, w.dtype,
+                          seqs=seqs, n_threads=cores)
+        c1 = time.perf_counter()
+        sample_bytes = int(per_seq[:n_seq].sum())
+        out["cpu_baseline"] = {"value": sample_bytes / (c1 - c0) / 1e9, "unit": "GB/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": "fp64 oracle, attention of the first %d of %d sequences (all heads, "
+                                         "full contexts, %.2f GB of KV), %.2f s wall" %
+                                         (n_seq, w.batch, sample_bytes / 1e9, c1 - c0)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

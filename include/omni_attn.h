@@ -1,0 +1,176 @@
+/*
+ * omni_attn.h — C ABI of the MI355X (gfx950) paged decode-attention library.
+ *
+ * The operation is the decode-phase attention of the paper's Background
+ * section ("Attention computation", Eq. 1): for every decoding request only
+ * the query q of its last token takes part,
+ *
+ *     Attention(q, K, V) = softmax(q K^T / sqrt(d_k)) V ,
+ *
+ * against the request's cached keys and values, the current token's own k, v
+ * included (the latency-model section counts a decode request's load as
+ * l_j + 1 tokens).  The KV cache is paged (the paper's engine is a paged-
+ * attention one).  Attention piggybacking computes parts of a request's
+ * attention in different places (GPU-resident context, context held by CPU
+ * hosts whose threads each compute a partial load and aggregate intermediate
+ * results — System Implementation, "CPU Attention"); the results come back
+ * through an output queue of per-layer attention rows and join the input of
+ * the following projection (Asynchronous CPU-GPU interaction).  This library
+ * is the GPU side of that data path:
+ *
+ *   omni_paged_decode_attn  attention of each sequence over a token range of
+ *                           its paged context, cut into chunks; one partial
+ *                           (O, LSE) per (sequence, chunk, query head);
+ *   omni_merge_partials     exact combination of partials of a sequence that
+ *                           come from up to four sources into the final row.
+ *
+ * General rules
+ *   - Every data pointer is DEVICE memory owned by the caller.  The library
+ *     allocates nothing, frees nothing and keeps no state between calls.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return without synchronising.
+ *   - The return value reports what the host can see: NULL pointers, bad
+ *     sizes, unsupported shapes, a failed launch.  Argument structs live in
+ *     host memory and are read before the call returns.
+ *   - Page indices are checked on the device: a block-table entry outside
+ *     [0, num_blocks) makes its 16 tokens count as absent (no access is made);
+ *     ctx_end is clamped to max_blocks_per_seq * block_size, ctx_begin to >= 0.
+ *   - Supported: block_size 16; head_dim 64 or 128; dtype fp32 or bf16;
+ *     num_q_heads a multiple of num_kv_heads with ratio G <= 16.
+ *
+ * Layouts (row-major, last index fastest)
+ *   q            [batch, num_q_heads, head_dim]
+ *   k_pool/v_pool[num_blocks, num_kv_heads, block_size, head_dim]
+ *                so the 16 x head_dim tile of one (page, kv head) is one
+ *                contiguous run (4 KiB for bf16, head_dim 128).  Pools must be
+ *                16-byte aligned.
+ *   block_table  [batch, max_blocks_per_seq] int32; logical token t of
+ *                sequence i is in page block_table[i][t / 16], slot t % 16.
+ *   query head j reads kv head j / G.
+ *
+ * Partials
+ *   A partial over a token set R is O_R = sum_{t in R} softmax_R(s)_t v_t
+ *   (normalised inside R) with LSE_R = ln sum_{t in R} exp(s_t), s_t =
+ *   sm_scale * <q, k_t>, natural logarithm.  Empty R: LSE = -inf and O is not
+ *   written.  Merging uses the identity of Eq. 1 over a disjoint union:
+ *   w_p = exp(LSE_p - max LSE), O = sum w_p O_p / sum w_p,
+ *   LSE = max LSE + ln sum w_p.  A partial with LSE = -inf has weight zero and
+ *   its O row is never read; a row with no weight at all gives O = 0,
+ *   LSE = -inf.
+ */
+#ifndef OMNI_ATTN_H
+#define OMNI_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OMNI_OK = 0,
+    OMNI_ERR_NULL = -1,        /* a required pointer is NULL                      */
+    OMNI_ERR_SHAPE = -2,       /* non-positive size, G not integral, bad chunking */
+    OMNI_ERR_DTYPE = -3,       /* dtype value not known                           */
+    OMNI_ERR_UNSUPPORTED = -4, /* valid but outside the supported set             */
+    OMNI_ERR_LAUNCH = -5       /* HIP reported an error at launch                 */
+} omni_status;
+
+typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype;
+
+/* kernel selection for omni_paged_decode_attn */
+typedef enum {
+    OMNI_KERNEL_AUTO = 0,      /* matrix-core kernel when the shape allows, else the vector one */
+    OMNI_KERNEL_VECTOR = 1,    /* vector-ALU kernel, any supported shape                        */
+    OMNI_KERNEL_MFMA = 2       /* matrix-core kernel: bf16, head_dim 128 (else UNSUPPORTED)      */
+} omni_kernel;
+
+typedef struct {
+    /* problem shape */
+    int32_t batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq;
+    int64_t num_blocks;            /* pages in each pool                                      */
+    int32_t qkv_dtype;             /* omni_dtype of q, k_pool, v_pool                         */
+    float   sm_scale;              /* multiplies q.k; 1/sqrt(head_dim) in Eq. 1               */
+    /* inputs (device) */
+    const void*    q;
+    const void*    k_pool;
+    const void*    v_pool;
+    const int32_t* block_table;
+    const int32_t* ctx_begin;      /* [batch] first token attended; NULL = all zero           */
+    const int32_t* ctx_end;        /* [batch] one past the last token attended                */
+    /* chunking: chunk c of sequence i covers tokens
+     * [ctx_begin[i] + c*chunk_tokens, min(ctx_end[i], ctx_begin[i] + (c+1)*chunk_tokens)).
+     * chunk_tokens = 0 means one chunk holding the whole range (max_chunks must be 1).
+     * Otherwise chunk_tokens is a positive multiple of block_size and max_chunks >= 1 is the
+     * chunk stride of the partial buffers; tokens beyond max_chunks chunks are NOT attended. */
+    int32_t chunk_tokens;
+    int32_t max_chunks;
+    /* outputs (device) */
+    float* part_o;                 /* [batch, max_chunks, num_q_heads, head_dim] fp32; may be
+                                      NULL if out_o is given and max_chunks == 1              */
+    float* part_lse;               /* [batch, max_chunks, num_q_heads] fp32                   */
+    void*  out_o;                  /* optional [batch, num_q_heads, head_dim] of out_dtype:   */
+    int32_t out_dtype;             /*   with max_chunks == 1 the single chunk's O is also     */
+    float* out_lse;                /*   written here as the final row (and LSE to out_lse if  */
+                                   /*   not NULL; an empty range writes O = 0, LSE = -inf)    */
+    int32_t kernel;                /* omni_kernel                                             */
+} omni_decode_args;
+
+/*
+ * Batched decode attention over a paged KV cache, emitting per-chunk partials
+ * (Eq. 1 restricted to each chunk; see "Partials" above).
+ * Errors: NULL (q, pools, block_table, ctx_end, or no output given), SHAPE,
+ * DTYPE, UNSUPPORTED, LAUNCH.  A batch of zero is OK and does nothing.
+ */
+omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream);
+
+/* One source of partial rows for the merge. */
+typedef struct {
+    const float*   o;                  /* [n_rows, num_q_heads, head_dim] fp32                 */
+    const float*   lse;                /* [n_rows, num_q_heads] fp32, natural log              */
+    const int32_t* row_offsets;        /* [batch+1] CSR: rows of sequence i are
+                                          row_offsets[i] .. row_offsets[i+1]-1; NULL = dense   */
+    int32_t        dense_rows_per_seq; /* dense: rows i*n .. i*n+n-1 belong to sequence i      */
+} omni_partial_src;
+
+/*
+ * Merge the partials of every (sequence, query head) found in srcs[0..n_srcs)
+ * (1 <= n_srcs <= 4; e.g. split-KV chunks of this GPU, partials computed by
+ * other hosts and returned through the output queue, GPU-computed tails) into
+ * out_o [batch, num_q_heads, head_dim] of out_dtype and, if not NULL,
+ * out_lse [batch, num_q_heads].  The srcs array is host memory, copied during
+ * the call.  Errors: NULL, SHAPE (n_srcs out of range, head_dim not 64/128 ...),
+ * DTYPE, LAUNCH.
+ */
+omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head_dim,
+                                const omni_partial_src* srcs, int32_t n_srcs,
+                                void* out_o, int32_t out_dtype, float* out_lse,
+                                void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* omni_status_string(omni_status s);
+
+/*
+ * Test aid for the block-table gather: copies the K and V rows of tokens
+ * [ctx_begin[seq], ctx_end[seq]) of one sequence (ranges clamped as above) to
+ * k_out / v_out [n_tokens, num_kv_heads, head_dim] in the pool's dtype, bit for
+ * bit.  Rows whose page index is out of range are filled with zero bytes.
+ */
+omni_status omni_debug_gather_kv(const omni_decode_args* a, int32_t seq, void* k_out, void* v_out,
+                                 void* hip_stream);
+
+/*
+ * Measurement aids.  omni_debug_stream_read reads `bytes` (multiple of 16) of
+ * device memory once with 16-byte loads and folds them into sink[0..3] (so the
+ * reads cannot be dropped): the streaming-read ceiling the attention kernel is
+ * compared with.  omni_debug_copy copies `bytes` (multiple of 16) from src to
+ * dst: the known-size kernel that calibrates the HBM byte counters.
+ */
+omni_status omni_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
+omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNI_ATTN_H */

@@ -1,0 +1,227 @@
+"""ctypes binding of libomni_attn.so: argument marshalling only.
+
+Functions carry the names of the C entry points declared in
+``include/omni_attn.h``; tensors are torch CUDA tensors used purely as device
+memory handles.  There is no fallback: if the library has not been built, or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libomni_attn.so")
+
+OMNI_F32, OMNI_BF16 = 0, 1
+OMNI_KERNEL_AUTO, OMNI_KERNEL_VECTOR, OMNI_KERNEL_MFMA = 0, 1, 2
+OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OMNI_ERR_LAUNCH = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ("omni_paged_decode_attn", "omni_merge_partials", "omni_status_string", "omni_debug_gather_kv",
+           "omni_debug_stream_read", "omni_debug_copy")
+
+
+class OmniError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, omni_status_string(status)))
+
+
+class omni_decode_args(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("num_blocks", ctypes.c_int64), ("qkv_dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+        ("q", ctypes.c_void_p), ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("ctx_begin", ctypes.c_void_p), ("ctx_end", ctypes.c_void_p),
+        ("chunk_tokens", ctypes.c_int32), ("max_chunks", ctypes.c_int32),
+        ("part_o", ctypes.c_void_p), ("part_lse", ctypes.c_void_p),
+        ("out_o", ctypes.c_void_p), ("out_dtype", ctypes.c_int32), ("out_lse", ctypes.c_void_p),
+        ("kernel", ctypes.c_int32),
+    ]
+
+
+class omni_partial_src(ctypes.Structure):
+    _fields_ = [("o", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("row_offsets", ctypes.c_void_p),
+                ("dense_rows_per_seq", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library (no GPU needed for loading).  Raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libomni_attn.so is not built (run `python -m paper_2603_12831_amd.build`); "
+                               "there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        lib.omni_paged_decode_attn.argtypes = [ctypes.POINTER(omni_decode_args), vp]
+        lib.omni_paged_decode_attn.restype = ctypes.c_int
+        lib.omni_merge_partials.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.POINTER(omni_partial_src), ctypes.c_int32, vp,
+                                            ctypes.c_int32, vp, vp]
+        lib.omni_merge_partials.restype = ctypes.c_int
+        lib.omni_status_string.argtypes = [ctypes.c_int]
+        lib.omni_status_string.restype = ctypes.c_char_p
+        lib.omni_debug_gather_kv.argtypes = [ctypes.POINTER(omni_decode_args), ctypes.c_int32, vp, vp, vp]
+        lib.omni_debug_gather_kv.restype = ctypes.c_int
+        lib.omni_debug_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        lib.omni_debug_stream_read.restype = ctypes.c_int
+        lib.omni_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.omni_debug_copy.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _dtype_code(t: torch.Tensor, name: str) -> int:
+    if t.dtype == torch.float32:
+        return OMNI_F32
+    if t.dtype == torch.bfloat16:
+        return OMNI_BF16
+    raise ValueError("%s must be float32 or bfloat16" % name)
+
+
+def omni_status_string(status: int) -> str:
+    return load_library().omni_status_string(int(status)).decode()
+
+
+def make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
+                     chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None, out_o=None,
+                     out_lse=None, kernel: int = OMNI_KERNEL_AUTO) -> omni_decode_args:
+    """Fill the C argument struct from tensors (shapes are taken from the tensors)."""
+    a = omni_decode_args()
+    a.batch, a.num_q_heads, a.head_dim = q.shape
+    a.num_blocks, a.num_kv_heads, a.block_size, d2 = k_pool.shape
+    if d2 != a.head_dim or tuple(v_pool.shape) != tuple(k_pool.shape):
+        raise ValueError("pool shapes do not match q / each other")
+    if block_table.shape[0] != a.batch or ctx_end.shape[0] != a.batch:
+        raise ValueError("block_table / ctx_end batch mismatch")
+    a.max_blocks_per_seq = block_table.shape[1]
+    a.qkv_dtype = _dtype_code(q, "q")
+    if k_pool.dtype != q.dtype or v_pool.dtype != q.dtype:
+        raise ValueError("q, k_pool, v_pool must share a dtype")
+    a.sm_scale = float(sm_scale)
+    a.q, a.k_pool, a.v_pool = _dev_ptr(q, "q"), _dev_ptr(k_pool, "k_pool"), _dev_ptr(v_pool, "v_pool")
+    a.block_table = _dev_ptr(block_table, "block_table", torch.int32)
+    a.ctx_begin = _dev_ptr(ctx_begin, "ctx_begin", torch.int32)
+    a.ctx_end = _dev_ptr(ctx_end, "ctx_end", torch.int32)
+    a.chunk_tokens, a.max_chunks = int(chunk_tokens), int(max_chunks)
+    if part_o is not None and part_o.numel() != a.batch * a.max_chunks * a.num_q_heads * a.head_dim:
+        raise ValueError("part_o has the wrong size")
+    if part_lse is not None and part_lse.numel() != a.batch * a.max_chunks * a.num_q_heads:
+        raise ValueError("part_lse has the wrong size")
+    a.part_o = _dev_ptr(part_o, "part_o", torch.float32)
+    a.part_lse = _dev_ptr(part_lse, "part_lse", torch.float32)
+    if out_o is not None:
+        if out_o.numel() != q.numel():
+            raise ValueError("out_o has the wrong size")
+        a.out_dtype = _dtype_code(out_o, "out_o")
+    a.out_o = _dev_ptr(out_o, "out_o")
+    if out_lse is not None and out_lse.numel() != a.batch * a.num_q_heads:
+        raise ValueError("out_lse has the wrong size")
+    a.out_lse = _dev_ptr(out_lse, "out_lse", torch.float32)
+    a.kernel = int(kernel)
+    return a
+
+
+def omni_paged_decode_attn(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
+                           chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None,
+                           out_o=None, out_lse=None, kernel: int = OMNI_KERNEL_AUTO, stream=None,
+                           check: bool = True) -> int:
+    a = make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, sm_scale=sm_scale,
+                         chunk_tokens=chunk_tokens, max_chunks=max_chunks, part_o=part_o, part_lse=part_lse,
+                         out_o=out_o, out_lse=out_lse, kernel=kernel)
+    return omni_paged_decode_attn_raw(a, stream, check)
+
+
+def omni_paged_decode_attn_raw(args: omni_decode_args, stream=None, check: bool = True) -> int:
+    st = load_library().omni_paged_decode_attn(ctypes.byref(args), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_paged_decode_attn")
+    return st
+
+
+PartialSrc = Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor], int]
+
+
+def make_partial_srcs(srcs: Sequence[PartialSrc], batch: int, num_q_heads: int, head_dim: int):
+    arr = (omni_partial_src * max(1, len(srcs)))()
+    for i, (o, lse, row_offsets, dense_rows) in enumerate(srcs):
+        n_rows = lse.numel() // num_q_heads
+        if o.numel() != n_rows * num_q_heads * head_dim:
+            raise ValueError("partial source %d: o / lse sizes disagree" % i)
+        if row_offsets is None and n_rows != batch * dense_rows:
+            raise ValueError("partial source %d: dense rows do not cover the batch" % i)
+        if row_offsets is not None and row_offsets.numel() != batch + 1:
+            raise ValueError("partial source %d: row_offsets must have batch+1 entries" % i)
+        arr[i].o = _dev_ptr(o, "src.o", torch.float32)
+        arr[i].lse = _dev_ptr(lse, "src.lse", torch.float32)
+        arr[i].row_offsets = _dev_ptr(row_offsets, "src.row_offsets", torch.int32)
+        arr[i].dense_rows_per_seq = int(dense_rows)
+    return arr
+
+
+def omni_merge_partials(batch: int, num_q_heads: int, head_dim: int, srcs: Sequence[PartialSrc], out_o,
+                        out_lse=None, stream=None, check: bool = True) -> int:
+    """srcs: sequence of (o, lse, row_offsets or None, dense_rows_per_seq)."""
+    arr = make_partial_srcs(srcs, batch, num_q_heads, head_dim)
+    if out_o.numel() != batch * num_q_heads * head_dim:
+        raise ValueError("out_o has the wrong size")
+    st = load_library().omni_merge_partials(batch, num_q_heads, head_dim, arr, len(srcs),
+                                            _dev_ptr(out_o, "out_o"), _dtype_code(out_o, "out_o"),
+                                            _dev_ptr(out_lse, "out_lse", torch.float32), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_merge_partials")
+    return st
+
+
+def omni_debug_gather_kv(args: omni_decode_args, seq: int, k_out, v_out, stream=None, check: bool = True) -> int:
+    st = load_library().omni_debug_gather_kv(ctypes.byref(args), int(seq), _dev_ptr(k_out, "k_out"),
+                                             _dev_ptr(v_out, "v_out"), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_debug_gather_kv")
+    return st
+
+
+def omni_debug_stream_read(src, sink, nbytes: Optional[int] = None, stream=None) -> int:
+    n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    if sink.numel() * sink.element_size() < 16 or n > src.numel() * src.element_size():
+        raise ValueError("sink needs 16 bytes; nbytes must not exceed src")
+    st = load_library().omni_debug_stream_read(_dev_ptr(src, "src"), n, _dev_ptr(sink, "sink"), _stream_ptr(stream))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_debug_stream_read")
+    return st
+
+
+def omni_debug_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> int:
+    n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    if n > dst.numel() * dst.element_size() or n > src.numel() * src.element_size():
+        raise ValueError("copy larger than its buffers")
+    st = load_library().omni_debug_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), n, _stream_ptr(stream))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_debug_copy")
+    return st

@@ -1,0 +1,133 @@
+// C ABI of libomni_attn: argument checks, flattening, kernel choice.
+#include <limits.h>
+
+#include "omni_internal.hpp"
+
+using namespace omni;
+
+namespace {
+
+bool dtype_ok(int32_t d) { return d == OMNI_F32 || d == OMNI_BF16; }
+
+// Checks shared by the decode entry point and the gather aid; fills `p`.
+omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_outputs)
+{
+    if (!a) return OMNI_ERR_NULL;
+    if (a->batch < 0 || a->num_q_heads <= 0 || a->num_kv_heads <= 0 || a->head_dim <= 0 ||
+        a->block_size <= 0 || a->max_blocks_per_seq <= 0 || a->num_blocks <= 0)
+        return OMNI_ERR_SHAPE;
+    if (a->num_q_heads % a->num_kv_heads != 0) return OMNI_ERR_SHAPE;
+    if (!dtype_ok(a->qkv_dtype)) return OMNI_ERR_DTYPE;
+    if (a->chunk_tokens < 0 || a->max_chunks < 1) return OMNI_ERR_SHAPE;
+    if (a->chunk_tokens == 0 && a->max_chunks != 1) return OMNI_ERR_SHAPE;
+    if (a->chunk_tokens % a->block_size != 0) return OMNI_ERR_SHAPE;
+    if (a->block_size != kBlockSize) return OMNI_ERR_UNSUPPORTED;
+    if (a->head_dim != 64 && a->head_dim != 128) return OMNI_ERR_UNSUPPORTED;
+    if (a->num_q_heads / a->num_kv_heads > 16) return OMNI_ERR_UNSUPPORTED;
+    if (a->batch > 65535 || a->max_chunks > 65535) return OMNI_ERR_UNSUPPORTED;
+    if ((long long)a->max_blocks_per_seq * kBlockSize > INT_MAX / 2) return OMNI_ERR_UNSUPPORTED;
+    if (!a->q || !a->k_pool || !a->v_pool || !a->block_table || !a->ctx_end) return OMNI_ERR_NULL;
+    if (need_outputs) {
+        if (!dtype_ok(a->out_dtype) && a->out_o) return OMNI_ERR_DTYPE;
+        const bool partials = a->part_o && a->part_lse;
+        if ((a->part_o == nullptr) != (a->part_lse == nullptr)) return OMNI_ERR_NULL;
+        if (!partials && !(a->out_o && a->max_chunks == 1)) return OMNI_ERR_NULL;
+    }
+    p.batch = a->batch; p.hq = a->num_q_heads; p.hkv = a->num_kv_heads; p.d = a->head_dim;
+    p.max_blocks = a->max_blocks_per_seq; p.group = a->num_q_heads / a->num_kv_heads;
+    p.num_blocks = a->num_blocks; p.sm_scale = a->sm_scale;
+    p.q = a->q; p.k_pool = a->k_pool; p.v_pool = a->v_pool; p.block_table = a->block_table;
+    p.ctx_begin = a->ctx_begin; p.ctx_end = a->ctx_end;
+    // "one chunk" = a chunk long enough for any clamped range
+    p.chunk_tokens = a->chunk_tokens ? a->chunk_tokens : a->max_blocks_per_seq * kBlockSize;
+    p.max_chunks = a->max_chunks;
+    p.part_o = a->part_o; p.part_lse = a->part_lse;
+    p.out_o = (a->max_chunks == 1) ? a->out_o : nullptr;
+    p.out_bf16 = a->out_dtype == OMNI_BF16;
+    p.out_lse = p.out_o ? a->out_lse : nullptr;
+    return OMNI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
+{
+    DecodeParams p;
+    omni_status st = flatten(a, p, true);
+    if (st != OMNI_OK) return st;
+    if (a->kernel != OMNI_KERNEL_AUTO && a->kernel != OMNI_KERNEL_VECTOR && a->kernel != OMNI_KERNEL_MFMA)
+        return OMNI_ERR_SHAPE;
+    if (p.batch == 0) return OMNI_OK;
+    const bool bf16 = a->qkv_dtype == OMNI_BF16;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    bool mfma = decode_mfma_supports(p, bf16);
+    if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return OMNI_ERR_UNSUPPORTED;
+    if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
+    hipError_t e = mfma ? launch_decode_mfma(p, s) : launch_decode_vector(p, bf16, s);
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head_dim,
+                                const omni_partial_src* srcs, int32_t n_srcs,
+                                void* out_o, int32_t out_dtype, float* out_lse, void* hip_stream)
+{
+    if (batch < 0 || num_q_heads <= 0 || n_srcs < 1 || n_srcs > 4) return OMNI_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return OMNI_ERR_SHAPE;
+    if (!dtype_ok(out_dtype)) return OMNI_ERR_DTYPE;
+    if (!srcs || !out_o) return OMNI_ERR_NULL;
+    MergeParams p;
+    for (int i = 0; i < n_srcs; ++i) {
+        if (!srcs[i].o || !srcs[i].lse) return OMNI_ERR_NULL;
+        if (!srcs[i].row_offsets && srcs[i].dense_rows_per_seq < 0) return OMNI_ERR_SHAPE;
+        p.src[i] = srcs[i];
+    }
+    for (int i = n_srcs; i < 4; ++i) p.src[i] = omni_partial_src{nullptr, nullptr, nullptr, 0};
+    p.n_srcs = n_srcs; p.batch = batch; p.hq = num_q_heads; p.d = head_dim;
+    p.out_bf16 = out_dtype == OMNI_BF16; p.out_o = out_o; p.out_lse = out_lse;
+    hipError_t e = launch_merge(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+const char* omni_status_string(omni_status s)
+{
+    switch (s) {
+        case OMNI_OK: return "OMNI_OK";
+        case OMNI_ERR_NULL: return "OMNI_ERR_NULL: a required pointer is NULL";
+        case OMNI_ERR_SHAPE: return "OMNI_ERR_SHAPE: bad size, head ratio or chunking";
+        case OMNI_ERR_DTYPE: return "OMNI_ERR_DTYPE: unknown dtype";
+        case OMNI_ERR_UNSUPPORTED: return "OMNI_ERR_UNSUPPORTED: shape outside the supported set";
+        case OMNI_ERR_LAUNCH: return "OMNI_ERR_LAUNCH: HIP launch failed";
+    }
+    return "OMNI_ERR_?: unknown status";
+}
+
+omni_status omni_debug_gather_kv(const omni_decode_args* a, int32_t seq, void* k_out, void* v_out, void* hip_stream)
+{
+    DecodeParams p;
+    omni_status st = flatten(a, p, false);
+    if (st != OMNI_OK) return st;
+    if (!k_out || !v_out) return OMNI_ERR_NULL;
+    if (seq < 0 || seq >= p.batch) return OMNI_ERR_SHAPE;
+    hipError_t e = launch_gather(p, a->qkv_dtype == OMNI_BF16, seq, k_out, v_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream)
+{
+    if (!src || !sink) return OMNI_ERR_NULL;
+    if (bytes % 16 != 0) return OMNI_ERR_SHAPE;
+    hipError_t e = launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream)
+{
+    if (!src || !dst) return OMNI_ERR_NULL;
+    if (bytes % 16 != 0) return OMNI_ERR_SHAPE;
+    hipError_t e = launch_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Merge of partial attention rows from up to four sources (split-KV chunks,
+// externally produced partials, GPU tails) into final rows.  The rule is the
+// exact identity of Eq. 1 (paper, Background) over a disjoint union of token
+// sets: w_p = exp(LSE_p - max LSE), O = sum w_p O_p / sum w_p,
+// LSE = max LSE + ln sum w_p.  This is the GPU-side aggregation of the
+// intermediate results that the paper's CPU attention threads produce.
+//
+// One thread owns four consecutive dims of one (sequence, head) row, so a row
+// is read with 16-byte loads by head_dim/4 adjacent lanes.  A partial whose
+// LSE is -inf is skipped without touching its O row.
+#include "omni_internal.hpp"
+
+namespace omni {
+namespace {
+
+__device__ __forceinline__ void src_rows(const omni_partial_src& s, int seq, int& r0, int& r1)
+{
+    if (s.row_offsets) { r0 = s.row_offsets[seq]; r1 = s.row_offsets[seq + 1]; }
+    else { r0 = seq * s.dense_rows_per_seq; r1 = r0 + s.dense_rows_per_seq; }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
+{
+    constexpr int kLanesPerRow = D / 4;
+    constexpr int kRowsPerBlock = 256 / kLanesPerRow;
+    const long long row = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / kLanesPerRow;
+    const int quad = threadIdx.x % kLanesPerRow;
+    if (row >= (long long)p.batch * p.hq) return;
+    const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
+
+    float m = -INFINITY;
+    for (int s = 0; s < p.n_srcs; ++s) {
+        int r0, r1;
+        src_rows(p.src[s], seq, r0, r1);
+        for (int r = r0; r < r1; ++r) m = fmaxf(m, p.src[s].lse[(long long)r * p.hq + head]);
+    }
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float wsum = 0.f;
+    if (m != -INFINITY) {
+        for (int s = 0; s < p.n_srcs; ++s) {
+            int r0, r1;
+            src_rows(p.src[s], seq, r0, r1);
+            for (int r = r0; r < r1; ++r) {
+                float lse = p.src[s].lse[(long long)r * p.hq + head];
+                if (lse == -INFINITY) continue;
+                float w = expf(lse - m);
+                float4 o = *reinterpret_cast<const float4*>(p.src[s].o + ((long long)r * p.hq + head) * D + quad * 4);
+                wsum += w;
+                acc.x = fmaf(w, o.x, acc.x); acc.y = fmaf(w, o.y, acc.y);
+                acc.z = fmaf(w, o.z, acc.z); acc.w = fmaf(w, o.w, acc.w);
+            }
+        }
+        float inv = 1.f / wsum;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    if (p.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
+        pk.y = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_o) + row * D + quad * 4) = pk;
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(p.out_o) + row * D + quad * 4) = acc;
+    }
+    if (p.out_lse && quad == 0) p.out_lse[row] = (m == -INFINITY) ? -INFINITY : m + logf(wsum);
+}
+
+}  // namespace
+
+hipError_t launch_merge(const MergeParams& p, hipStream_t s)
+{
+    long long rows = (long long)p.batch * p.hq;
+    if (rows == 0) return hipSuccess;
+    if (p.d == 64) {
+        unsigned grid = (unsigned)((rows + 15) / 16);
+        hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, s, p);
+    } else {
+        unsigned grid = (unsigned)((rows + 7) / 8);
+        hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace omni

@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of libomni_attn.
+// Device helpers are plain inline functions; launchers are defined next to
+// their kernels and called from api.hip.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "omni_attn.h"
+
+namespace omni {
+
+constexpr int kBlockSize = 16;     // tokens per KV page
+constexpr int kWave = 64;          // CDNA wavefront width
+
+// Flattened, validated form of omni_decode_args handed to the kernels.
+struct DecodeParams {
+    int batch, hq, hkv, d, max_blocks, group;
+    long long num_blocks;
+    float sm_scale;
+    const void* q;
+    const void* k_pool;
+    const void* v_pool;
+    const int* block_table;
+    const int* ctx_begin;          // may be null
+    const int* ctx_end;
+    int chunk_tokens;              // > 0 here: "one chunk" is expressed as INT_MAX/2 rounded to pages
+    int max_chunks;
+    float* part_o;                 // may be null
+    float* part_lse;               // may be null
+    void* out_o;                   // may be null; only honoured when max_chunks == 1
+    int out_bf16;
+    float* out_lse;                // may be null
+};
+
+struct MergeParams {
+    omni_partial_src src[4];
+    int n_srcs, batch, hq, d, out_bf16;
+    void* out_o;
+    float* out_lse;
+};
+
+// ---- device helpers -------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Token range of sequence `seq`, clamped so that every touched table entry exists.
+__device__ __forceinline__ void seq_range(const DecodeParams& p, int seq, int& b, int& e)
+{
+    b = p.ctx_begin ? p.ctx_begin[seq] : 0;
+    e = p.ctx_end[seq];
+    if (b < 0) b = 0;
+    long long cap = (long long)p.max_blocks * kBlockSize;
+    if (e > cap) e = (int)cap;
+}
+
+// Range of chunk c inside [b, e); empty ranges come back with ce <= cb.
+__device__ __forceinline__ void chunk_range(const DecodeParams& p, int b, int e, int c, int& cb, int& ce)
+{
+    long long lo = (long long)b + (long long)c * p.chunk_tokens;
+    long long hi = lo + p.chunk_tokens;
+    cb = lo < e ? (int)lo : e;
+    ce = hi < e ? (int)hi : e;
+}
+
+// ---- launchers (each defined beside its kernel) ---------------------------
+hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t s);
+bool decode_mfma_supports(const DecodeParams& p, bool bf16);
+hipError_t launch_merge(const MergeParams& p, hipStream_t s);
+hipError_t launch_gather(const DecodeParams& p, bool bf16, int seq, void* k_out, void* v_out, hipStream_t s);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+
+}  // namespace omni

@@ -1,0 +1,94 @@
+"""Device-side plumbing around the binding: upload a workload, allocate the
+partial / output buffers, issue the decode calls and the merge.  No arithmetic
+of the method happens here — every step runs in the HIP library."""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding
+from .workloads import Workload
+
+
+def to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
+    """Upload raw bits: uint16 arrays are bf16 patterns, float32 arrays are fp32."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+class DeviceWorkload:
+    """A workload resident in HBM plus the buffers one pass of the hot path writes."""
+
+    def __init__(self, w: Workload, device="cuda:0", out_dtype: Optional[str] = None,
+                 ext_o: Optional[np.ndarray] = None, ext_lse: Optional[np.ndarray] = None,
+                 ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1):
+        self.w = w
+        self.device = torch.device(device)
+        k_pool, v_pool, table = w.device_views()
+        self.q = to_device(w.q, w.dtype, self.device)
+        # several physical copies of the pools let a timing loop defeat cache residency
+        self.k_pools = [to_device(k_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
+        self.v_pools = [to_device(v_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
+        self.block_table = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).to(self.device)
+        B, Hq, D = w.batch, w.num_q_heads, w.head_dim
+        self.calls = []
+        for c in w.calls:
+            self.calls.append(dict(
+                begin=torch.from_numpy(np.ascontiguousarray(c.ctx_begin, dtype=np.int32)).to(self.device),
+                end=torch.from_numpy(np.ascontiguousarray(c.ctx_end, dtype=np.int32)).to(self.device),
+                chunk_tokens=c.chunk_tokens, max_chunks=c.max_chunks,
+                part_o=torch.empty((B, c.max_chunks, Hq, D), dtype=torch.float32, device=self.device),
+                part_lse=torch.empty((B, c.max_chunks, Hq), dtype=torch.float32, device=self.device)))
+        self.ext = None
+        if ext_o is not None:
+            self.ext = (torch.from_numpy(np.ascontiguousarray(ext_o, dtype=np.float32)).to(self.device),
+                        torch.from_numpy(np.ascontiguousarray(ext_lse, dtype=np.float32)).to(self.device),
+                        torch.from_numpy(np.ascontiguousarray(ext_offsets, dtype=np.int32)).to(self.device), 0)
+        od = out_dtype or w.out_dtype
+        self.out_o = torch.empty((B, Hq, D), dtype=torch.bfloat16 if od == "bf16" else torch.float32,
+                                 device=self.device)
+        self.out_lse = torch.empty((B, Hq), dtype=torch.float32, device=self.device)
+        # a single one-chunk call with nothing else to merge writes the final rows itself
+        self.direct = len(self.calls) == 1 and self.calls[0]["max_chunks"] == 1 and self.ext is None
+
+    def poison_outputs(self):
+        """Fill every output with NaN so that stale data cannot pass a check."""
+        for c in self.calls:
+            c["part_o"].fill_(float("nan"))
+            c["part_lse"].fill_(float("nan"))
+        self.out_o.fill_(float("nan"))
+        self.out_lse.fill_(float("nan"))
+
+    def run_attention(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
+        w = self.w
+        for c in self.calls:
+            binding.omni_paged_decode_attn(
+                self.q, self.k_pools[pool], self.v_pools[pool], self.block_table, c["begin"], c["end"],
+                sm_scale=w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
+                part_o=None if self.direct else c["part_o"], part_lse=None if self.direct else c["part_lse"],
+                out_o=self.out_o if self.direct else None, out_lse=self.out_lse if self.direct else None,
+                kernel=kernel, stream=stream)
+
+    def merge_sources(self) -> List:
+        srcs = [self.ext] if self.ext is not None else []
+        srcs += [(c["part_o"], c["part_lse"], None, c["max_chunks"]) for c in self.calls]
+        return srcs
+
+    def run_merge(self, stream=None):
+        if self.direct:
+            return
+        w = self.w
+        binding.omni_merge_partials(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(), self.out_o,
+                                    self.out_lse, stream=stream)
+
+    def run(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
+        """One pass of the whole hot path: every decode call, then the merge."""
+        self.run_attention(kernel, pool, stream)
+        self.run_merge(stream)
+
+    def results(self):
+        torch.cuda.synchronize(self.device)
+        return self.out_o.float().cpu().numpy().astype(np.float64), self.out_lse.cpu().numpy().astype(np.float64)

@@ -1,0 +1,395 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle
+on the same seeded inputs.
+
+Tolerances (max abs error on O and on LSE, compared on fp32 outputs unless the
+config asks for bf16 output):
+  * fp32 inputs: 1e-5;
+  * bf16 inputs with fp32 accumulation: 2e-3.
+Integer work (which pages and slots are read) is checked bit-exactly through
+the gather aid and through attention over integer-coded values.
+"""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_2603_12831_amd import binding, workloads as wl
+from paper_2603_12831_amd.runner import DeviceWorkload, to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-3}
+THREADS = 16
+KERNELS = [binding.OMNI_KERNEL_VECTOR, binding.OMNI_KERNEL_AUTO]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m gpu on an MI355X box)")
+    binding.load_library()
+
+
+def union_range(w):
+    b = np.min(np.stack([c.ctx_begin for c in w.calls]), axis=0)
+    e = np.max(np.stack([c.ctx_end for c in w.calls]), axis=0)
+    return b, e
+
+
+def expected_full(w, begin=None, end=None, seqs=None, heads=None):
+    if begin is None:
+        begin, end = union_range(w)
+        if w.ext_ranges is not None:
+            begin = np.zeros_like(begin)
+    return oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, begin, end, w.sm_scale, w.dtype,
+                             seqs=seqs, heads=heads, n_threads=THREADS)
+
+
+def ext_partials_from_oracle(w):
+    """Externally produced partials of a hybrid batch: the oracle's fp64 partial over each
+    prefix piece, rounded to fp32 (the format such partials arrive in)."""
+    items = []
+    for i, ranges in enumerate(w.ext_ranges):
+        for (b, e) in ranges:
+            for h in range(w.num_q_heads):
+                items.append((i, h, b, e))
+    o, lse = oracle.paged_attn_items(w.q, w.k_pool, w.v_pool, w.block_table, items, w.sm_scale, w.dtype,
+                                     n_threads=THREADS)
+    n = len(items) // w.num_q_heads
+    return (o.reshape(n, w.num_q_heads, w.head_dim).astype(np.float32),
+            lse.reshape(n, w.num_q_heads).astype(np.float32), wl.ext_row_offsets(w))
+
+
+def check(got_o, got_l, exp_o, exp_l, tol, what=""):
+    assert got_o.shape == exp_o.shape and got_l.shape == exp_l.shape
+    fin = np.isfinite(exp_l)
+    assert np.array_equal(np.isfinite(got_l), fin), "%s: finite pattern of LSE differs" % what
+    assert np.all(got_l[~fin] == -np.inf)
+    assert np.all(np.isfinite(got_o)), "%s: non-finite O" % what
+    eo = float(np.max(np.abs(got_o - exp_o))) if got_o.size else 0.0
+    el = float(np.max(np.abs(got_l[fin] - exp_l[fin]))) if fin.any() else 0.0
+    assert eo <= tol and el <= tol, "%s: max abs err O %.3g LSE %.3g > %.1g" % (what, eo, el, tol)
+    return eo, el
+
+
+def run_and_check(w, kernel, out_dtype="f32", tol=None, ext=None, expected=None):
+    ext = ext or (None, None, None)
+    dw = DeviceWorkload(w, out_dtype=out_dtype, ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2])
+    dw.poison_outputs()
+    dw.run(kernel=kernel)
+    got_o, got_l = dw.results()
+    exp_o, exp_l = expected if expected is not None else expected_full(w)
+    return check(got_o, got_l, exp_o, exp_l, tol or TOL[w.dtype], w.name), dw
+
+
+# ---------------------------------------------------------------------------
+# config 1 (tiny fp32, two chunks per sequence, merged) and its partials
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_cfg1_merged_and_partials(kernel):
+    w = wl.make_cfg1()
+    (_, dw) = run_and_check(w, kernel)
+    for c, dc in zip(w.calls, dw.calls):
+        exp_o, exp_l = expected_full(w, c.ctx_begin, c.ctx_end)
+        po = dc["part_o"].cpu().numpy().astype(np.float64)[:, 0]
+        pl = dc["part_lse"].cpu().numpy().astype(np.float64)[:, 0]
+        check(po, pl, exp_o, exp_l, 1e-5, "cfg1 partial")
+
+
+# ---------------------------------------------------------------------------
+# scaled-down versions of configs 2-5: several pages per wave, ragged tails
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_small_cfg2_direct_bf16_output(kernel):
+    w = wl.make_cfg2(batch=5, lo=30, hi=700)
+    run_and_check(w, kernel, out_dtype="bf16")
+    run_and_check(w, kernel, out_dtype="f32")
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("chunk", [64, 256, 1024])
+def test_small_cfg3_chunked(kernel, chunk):
+    w = wl.make_cfg3(batch=12, median=300, lo=1, hi=1500, chunk_tokens=chunk)
+    (_, dw) = run_and_check(w, kernel)
+    # every partial against the oracle's partial over the same chunk
+    c = w.calls[0]
+    po = dw.calls[0]["part_o"].cpu().numpy().astype(np.float64)
+    pl = dw.calls[0]["part_lse"].cpu().numpy().astype(np.float64)
+    for ci in range(c.max_chunks):
+        b = np.minimum(c.ctx_begin + ci * chunk, c.ctx_end)
+        e = np.minimum(b + chunk, c.ctx_end)
+        exp_o, exp_l = expected_full(w, b, e)
+        live = e > b
+        assert np.all(pl[~live, ci] == -np.inf)
+        check(po[live, ci], pl[live, ci], exp_o[live], exp_l[live], 2e-3, "chunk %d" % ci)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_small_cfg5_wide_softmax_range(kernel):
+    w = wl.make_cfg5(batch=2, ctx=2048 + 48, chunk_tokens=256)
+    run_and_check(w, kernel)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_small_cfg4_hybrid(kernel):
+    w = wl.make_cfg4(n_ls=3, n_be=9, ls_lo=20, ls_hi=300, be_lo=300, be_hi=900, tail_lo=5, tail_hi=70)
+    run_and_check(w, kernel, ext=ext_partials_from_oracle(w))
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("shape", [(8, 8, 64), (8, 1, 128), (16, 1, 64), (6, 3, 128), (4, 4, 128), (32, 2, 128)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_head_layouts(kernel, shape, dtype):
+    hq, hkv, d = shape
+    w = wl.make_generic(21, [1, 16, 17, 200, 333], hq, hkv, d, dtype=dtype, chunk_tokens=128, pool_factor=1.5)
+    run_and_check(w, kernel)
+
+
+# ---------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_edge_lengths_and_offsets(kernel, dtype):
+    lengths = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 0, 129, 1000]
+    begins = [0, 1, 14, 0, 16, 5, 31, 32, 0, 63, 17, 99, 0, 128, 333]
+    w = wl.make_generic(31, np.maximum(lengths, 1), 8, 2, 128, dtype=dtype, pool_factor=2.0)
+    w.calls[0].ctx_end = np.array(lengths, dtype=np.int32)
+    w.calls[0].ctx_begin = np.array(begins, dtype=np.int32)
+    run_and_check(w, kernel)
+    # the same ranges, chunked: chunk boundaries relative to a non-aligned begin
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 64, 16
+    run_and_check(w, kernel)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_empty_and_reversed_ranges_give_zero_and_minus_inf(kernel):
+    w = wl.make_generic(32, [40, 40, 40], 4, 2, 128, dtype="bf16")
+    w.calls[0].ctx_begin = np.array([0, 40, 30], dtype=np.int32)
+    w.calls[0].ctx_end = np.array([0, 40, 10], dtype=np.int32)
+    for chunk, mc in [(0, 1), (16, 4)]:
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, mc
+        dw = DeviceWorkload(w, out_dtype="f32")
+        dw.poison_outputs()
+        dw.run(kernel=kernel)
+        o, l = dw.results()
+        assert np.all(o == 0) and np.all(l == -np.inf)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_chunks_beyond_max_chunks_are_not_attended(kernel):
+    w = wl.make_generic(33, [300, 90], 8, 2, 128, dtype="bf16")
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 64, 2
+    exp = expected_full(w, np.zeros(2, dtype=np.int32), np.array([128, 90], dtype=np.int32))
+    run_and_check(w, kernel, expected=exp)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_absent_pages_and_clamped_ranges(kernel):
+    """A table entry outside the pool removes its 16 tokens; ctx_end beyond the table is clamped."""
+    w = wl.make_generic(34, [160, 64], 8, 2, 128, dtype="bf16")
+    bt = w.block_table.copy()
+    bt[0, 3] = -1
+    bt[0, 7] = w.num_blocks + 5
+    w2 = wl.make_generic(34, [160, 64], 8, 2, 128, dtype="bf16")
+    w2.block_table = bt
+    w2.calls[0].ctx_end = np.array([160, 100000], dtype=np.int32)      # row 1 has 4 pages: clamps to 64
+    # expected: merge of the oracle's partials over the surviving ranges
+    pieces = [(0, 48), (64, 112), (128, 160)]
+    o0, l0 = [], []
+    for (b, e) in pieces:
+        o, l = expected_full(w, np.array([b, 0]), np.array([e, 0]), seqs=[0])
+        o0.append(o[0]); l0.append(l[0])
+    exp_o, exp_l = expected_full(w)
+    for h in range(w.num_q_heads):
+        mo, ml = oracle.merge(np.stack([x[h] for x in o0]), [x[h] for x in l0], [0, 3])
+        exp_o[0, h], exp_l[0, h] = mo[0], ml[0]
+    run_and_check(w2, kernel, expected=(exp_o, exp_l))
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_garbage_outside_the_range_is_never_used(kernel):
+    """Slots past ctx_end, slots before ctx_begin and unused pages hold NaN: results unchanged."""
+    w = wl.make_generic(35, [5, 40, 100, 257], 8, 2, 128, dtype="bf16", pool_factor=1.5)
+    begins = np.array([0, 7, 33, 1], dtype=np.int32)
+    w.calls[0].ctx_begin = begins
+    exp = expected_full(w)
+    nan = np.uint16(0x7FC0)
+    keep = np.zeros(w.k_pool.shape[:1] + (16,), dtype=bool)
+    for i, L in enumerate(w.ctx_len):
+        for t in range(int(begins[i]), int(L)):
+            keep[w.block_table[i, t // 16], t % 16] = True
+    for pool in (w.k_pool, w.v_pool):
+        pool[~keep[:, None, :].repeat(w.num_kv_heads, axis=1)] = nan
+    for chunk, mc in [(0, 1), (32, 9)]:
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, mc
+        run_and_check(w, kernel, expected=exp)
+
+
+# ---------------------------------------------------------------------------
+# integer work: gather and index-revealing attention are bit-exact
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gather_is_bit_exact(dtype):
+    w = wl.make_generic(41, [1, 16, 17, 100, 511], 8, 2, 64, dtype=dtype, pool_factor=2.0)
+    begins = np.array([0, 0, 3, 16, 255], dtype=np.int32)
+    w.calls[0].ctx_begin = begins
+    dw = DeviceWorkload(w)
+    c = dw.calls[0]
+    args = binding.make_decode_args(dw.q, dw.k_pools[0], dw.v_pools[0], dw.block_table, c["begin"], c["end"],
+                                    sm_scale=w.sm_scale, part_o=c["part_o"], part_lse=c["part_lse"])
+    for i, L in enumerate(w.ctx_len):
+        n = int(L - begins[i])
+        k_out = torch.zeros((n, w.num_kv_heads, w.head_dim), dtype=dw.q.dtype, device=dw.device)
+        v_out = torch.zeros_like(k_out)
+        binding.omni_debug_gather_kv(args, i, k_out, v_out)
+        torch.cuda.synchronize()
+        ek, ev = oracle.gather_kv(w.k_pool, w.v_pool, w.block_table, i, int(begins[i]), int(L))
+        view = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if dtype == "bf16" else \
+               (lambda t: t.cpu().numpy())
+        assert np.array_equal(view(k_out).view(np.uint8), ek.view(np.uint8))
+        assert np.array_equal(view(v_out).view(np.uint8), ev.view(np.uint8))
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_index_revealing_attention_is_exact(kernel, dtype):
+    """q = 0 makes every weight exactly 1/n; V rows hold small integer codes of (sequence, token),
+    distinct per dim group, so n * O must be the exact integer sum of the codes of the tokens read."""
+    lengths = [1, 16, 17, 64, 128, 250]
+    w = wl.make_generic(42, lengths, 8, 2, 128, dtype=dtype, pool_factor=2.0)
+    begins = np.array([0, 0, 5, 16, 1, 100], dtype=np.int32)
+    w.calls[0].ctx_begin = begins
+    q = np.zeros(w.q.shape, dtype=np.float32)
+    v = np.full(w.v_pool.shape, 200.0, dtype=np.float32)      # a wrong page or slot shows up as 200
+    for i, L in enumerate(lengths):
+        for t in range(L):
+            v[w.block_table[i, t // 16], :, t % 16, :] = (t % 64) + (i % 2)          # <= 64: exact in bf16
+    w.q = q if dtype == "f32" else wl.f32_to_bf16_bits(q)
+    w.v_pool = v if dtype == "f32" else wl.f32_to_bf16_bits(v)
+    dw = DeviceWorkload(w, out_dtype="f32")
+    dw.run(kernel=kernel)
+    o, lse = dw.results()
+    for i, L in enumerate(lengths):
+        n = L - int(begins[i])
+        want = sum((t % 64) + (i % 2) for t in range(int(begins[i]), L))
+        # power-of-two counts divide exactly; otherwise allow the division's rounding only
+        assert np.all(np.abs(o[i] * n - want) <= 1e-6 * max(1, want) * 8), (i, o[i, 0, 0] * n, want)
+        assert np.all(np.abs(lse[i] - math.log(n)) < 1e-6)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_deterministic_and_placement_independent(kernel):
+    w = wl.make_cfg3(batch=8, median=400, lo=10, hi=1500, chunk_tokens=256)
+    dw = DeviceWorkload(w, out_dtype="f32")
+    dw.run(kernel=kernel)
+    o1, l1 = dw.results()
+    dw.poison_outputs()
+    dw.run(kernel=kernel)
+    o2, l2 = dw.results()
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    # move every page to a new physical home, table updated: bit-identical outputs
+    perm = np.random.default_rng(0).permutation(w.num_blocks)
+    k2, v2 = np.empty_like(w.k_pool), np.empty_like(w.v_pool)
+    k2[perm], v2[perm] = w.k_pool, w.v_pool
+    w.k_pool, w.v_pool = k2, v2
+    w.block_table = np.where(w.block_table >= 0, perm[np.maximum(w.block_table, 0)], -1).astype(np.int32)
+    dw3 = DeviceWorkload(w, out_dtype="f32")
+    dw3.run(kernel=kernel)
+    o3, l3 = dw3.results()
+    assert np.array_equal(o1, o3) and np.array_equal(l1, l3)
+
+
+# ---------------------------------------------------------------------------
+# the merge on its own
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_merge_random_sources(d, out_dtype):
+    rng = np.random.default_rng(50 + d)
+    B, H = 37, 6
+    dev = torch.device("cuda:0")
+    # source 0: CSR with 0..5 rows per sequence; source 1: dense 3 rows; source 2: dense 1 row; source 3: CSR
+    srcs_np, kinds = [], ("csr", 3, 1, "csr")
+    for kind in kinds:
+        if kind == "csr":
+            counts = rng.integers(0, 6, size=B)
+            off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        else:
+            off = np.arange(B + 1, dtype=np.int32) * kind
+        n = int(off[-1])
+        o = rng.standard_normal((n, H, d)).astype(np.float32)
+        lse = (rng.standard_normal((n, H)) * 6).astype(np.float32)
+        lse[rng.random((n, H)) < 0.25] = -np.inf
+        for i in (0, 11):                                            # sequences with no live partial at all
+            lse[off[i]:off[i + 1]] = -np.inf
+        o[lse == -np.inf] = np.nan                                   # must never be read
+        srcs_np.append((o, lse, off))
+    srcs_t = [(torch.from_numpy(o).to(dev), torch.from_numpy(lse).to(dev),
+               torch.from_numpy(off).to(dev) if kind == "csr" else None, 0 if kind == "csr" else kind)
+              for (o, lse, off), kind in zip(srcs_np, kinds)]
+    for n_srcs in (1, 2, 4):
+        out_o = torch.full((B, H, d), float("nan"), dtype=out_dtype, device=dev)
+        out_l = torch.full((B, H), float("nan"), dtype=torch.float32, device=dev)
+        binding.omni_merge_partials(B, H, d, srcs_t[:n_srcs], out_o, out_l)
+        torch.cuda.synchronize()
+        po, pl, offs = [], [], [0]
+        for i in range(B):
+            for h in range(H):
+                for (o, lse, off) in srcs_np[:n_srcs]:
+                    po.append(np.nan_to_num(o[off[i]:off[i + 1], h], nan=0.0))
+                    pl.append(lse[off[i]:off[i + 1], h])
+                offs.append(offs[-1] + sum(int(s[2][i + 1] - s[2][i]) for s in srcs_np[:n_srcs]))
+        exp_o, exp_l = oracle.merge(np.concatenate(po), np.concatenate(pl), offs)
+        tol = 1e-5 if out_dtype == torch.float32 else 2.0 ** -8 * 5
+        check(out_o.float().cpu().numpy().astype(np.float64).reshape(B * H, d),
+              out_l.cpu().numpy().astype(np.float64).reshape(B * H), exp_o, exp_l, tol, "merge")
+        assert np.all(exp_l[:H] == -np.inf)                          # sequence 0 had nothing live
+        # without the LSE output
+        out2 = torch.full((B, H, d), float("nan"), dtype=out_dtype, device=dev)
+        binding.omni_merge_partials(B, H, d, srcs_t[:n_srcs], out2, None)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, out_o)
+
+
+# ---------------------------------------------------------------------------
+# full-size configurations, in the launch configuration the benchmark times
+# ---------------------------------------------------------------------------
+def test_full_cfg2():
+    w = wl.make_cfg2(workers=THREADS)
+    (eo, el), _ = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="bf16")
+    print("cfg2 max abs err O %.3g LSE %.3g" % (eo, el))
+
+
+def test_full_cfg3():
+    w = wl.make_cfg3(workers=THREADS)
+    (eo, el), dw = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="f32")
+    print("cfg3 max abs err O %.3g LSE %.3g" % (eo, el))
+    # the bf16 output the config asks for is the correctly rounded fp32 result, up to one step
+    exp_o, _ = expected_full(w)
+    dwb = DeviceWorkload(w, out_dtype="bf16")
+    dwb.run()
+    ob, _ = dwb.results()
+    assert np.max(np.abs(ob - exp_o) / np.maximum(np.abs(exp_o), 2.0 ** -6)) <= 2.0 ** -8 + 1e-3
+
+
+def test_full_cfg4():
+    w = wl.make_cfg4(workers=THREADS)
+    (eo, el), _ = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="f32", ext=ext_partials_from_oracle(w))
+    print("cfg4 max abs err O %.3g LSE %.3g" % (eo, el))
+
+
+def test_full_cfg5_sampled_sequences():
+    w = wl.make_cfg5(workers=THREADS)
+    dw = DeviceWorkload(w, out_dtype="f32")
+    dw.poison_outputs()
+    dw.run()
+    got_o, got_l = dw.results()
+    assert np.all(np.isfinite(got_o)) and np.all(np.isfinite(got_l))
+    seqs = [0, 7, 13, 31]                                            # every head of four sequences
+    exp_o, exp_l = expected_full(w, seqs=seqs)
+    eo, el = check(got_o[seqs], got_l[seqs], exp_o, exp_l, 2e-3, "cfg5")
+    print("cfg5 max abs err O %.3g LSE %.3g" % (eo, el))
