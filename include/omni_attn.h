@@ -26,7 +26,8 @@
  *
  * General rules
  *   - Every data pointer is DEVICE memory owned by the caller.  The library
- *     allocates nothing, frees nothing and keeps no state between calls.
+ *     allocates nothing, frees nothing and keeps no state between calls; the
+ *     only scratch it ever uses is the optional workspace the caller passes.
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and return without synchronising.
  *   - The return value reports what the host can see: NULL pointers, bad
@@ -115,15 +116,41 @@ typedef struct {
     float* out_lse;                /*   written here as the final row (and LSE to out_lse if  */
                                    /*   not NULL; an empty range writes O = 0, LSE = -inf)    */
     int32_t kernel;                /* omni_kernel                                             */
+    /* optional scratch for the matrix-core kernel's work list (device memory, caller-owned,
+     * at least omni_decode_workspace_bytes(batch, max_chunks) bytes, 16-byte aligned, contents
+     * need not survive between calls).  With it the kernel runs in its persistent form: non-empty
+     * chunks are listed longest-first and drawn by resident workgroups.  NULL selects the plain
+     * grid form.  Two calls that may overlap in time (different streams) need distinct
+     * workspaces.  The vector kernel ignores it.                                              */
+    void*    workspace;
+    uint64_t workspace_bytes;
+    /* non-zero: the workspace already holds the work list of exactly these ranges and this
+     * chunking, written by omni_decode_plan (or by an earlier call with the same ranges): the
+     * list is reused instead of rebuilt.  The list depends only on batch, ctx_begin, ctx_end,
+     * max_blocks_per_seq, chunk_tokens and max_chunks, so one plan serves the attention calls
+     * of every layer of a decoding iteration.                                                 */
+    int32_t  workspace_planned;
 } omni_decode_args;
 
 /*
  * Batched decode attention over a paged KV cache, emitting per-chunk partials
  * (Eq. 1 restricted to each chunk; see "Partials" above).
- * Errors: NULL (q, pools, block_table, ctx_end, or no output given), SHAPE,
- * DTYPE, UNSUPPORTED, LAUNCH.  A batch of zero is OK and does nothing.
+ * Errors: NULL (q, pools, block_table, ctx_end, or no output given), SHAPE
+ * (also a workspace that is too small or misaligned), DTYPE, UNSUPPORTED,
+ * LAUNCH.  A batch of zero is OK and does nothing.
  */
 omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream);
+
+/* Bytes of workspace the persistent form needs for this batch and chunk stride (0 if either is <= 0). */
+uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks);
+
+/*
+ * Build the work list for `a` into a->workspace on the stream, without computing attention: the
+ * non-empty (sequence, chunk) ranges in longest-first order.  Reads only the shape, chunking,
+ * ctx_begin and ctx_end; a following omni_paged_decode_attn with the same ranges may set
+ * workspace_planned.  Errors: as omni_paged_decode_attn, plus NULL if there is no workspace.
+ */
+omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream);
 
 /* One source of partial rows for the merge. */
 typedef struct {

@@ -20,8 +20,8 @@ OMNI_F32, OMNI_BF16 = 0, 1
 OMNI_KERNEL_AUTO, OMNI_KERNEL_VECTOR, OMNI_KERNEL_MFMA = 0, 1, 2
 OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OMNI_ERR_LAUNCH = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("omni_paged_decode_attn", "omni_merge_partials", "omni_status_string", "omni_debug_gather_kv",
-           "omni_debug_stream_read", "omni_debug_copy")
+EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
+           "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy")
 
 
 class OmniError(RuntimeError):
@@ -41,6 +41,8 @@ class omni_decode_args(ctypes.Structure):
         ("part_o", ctypes.c_void_p), ("part_lse", ctypes.c_void_p),
         ("out_o", ctypes.c_void_p), ("out_dtype", ctypes.c_int32), ("out_lse", ctypes.c_void_p),
         ("kernel", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_uint64),
+        ("workspace_planned", ctypes.c_int32),
     ]
 
 
@@ -63,6 +65,10 @@ def load_library() -> ctypes.CDLL:
         vp = ctypes.c_void_p
         lib.omni_paged_decode_attn.argtypes = [ctypes.POINTER(omni_decode_args), vp]
         lib.omni_paged_decode_attn.restype = ctypes.c_int
+        lib.omni_decode_plan.argtypes = [ctypes.POINTER(omni_decode_args), vp]
+        lib.omni_decode_plan.restype = ctypes.c_int
+        lib.omni_decode_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.omni_decode_workspace_bytes.restype = ctypes.c_uint64
         lib.omni_merge_partials.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                             ctypes.POINTER(omni_partial_src), ctypes.c_int32, vp,
                                             ctypes.c_int32, vp, vp]
@@ -111,7 +117,8 @@ def omni_status_string(status: int) -> str:
 
 def make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
                      chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None, out_o=None,
-                     out_lse=None, kernel: int = OMNI_KERNEL_AUTO) -> omni_decode_args:
+                     out_lse=None, kernel: int = OMNI_KERNEL_AUTO, workspace=None,
+                     workspace_planned: bool = False) -> omni_decode_args:
     """Fill the C argument struct from tensors (shapes are taken from the tensors)."""
     a = omni_decode_args()
     a.batch, a.num_q_heads, a.head_dim = q.shape
@@ -145,16 +152,20 @@ def make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_s
         raise ValueError("out_lse has the wrong size")
     a.out_lse = _dev_ptr(out_lse, "out_lse", torch.float32)
     a.kernel = int(kernel)
+    a.workspace = _dev_ptr(workspace, "workspace")
+    a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a.workspace_planned = 1 if workspace_planned else 0
     return a
 
 
 def omni_paged_decode_attn(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
                            chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None,
-                           out_o=None, out_lse=None, kernel: int = OMNI_KERNEL_AUTO, stream=None,
-                           check: bool = True) -> int:
+                           out_o=None, out_lse=None, kernel: int = OMNI_KERNEL_AUTO, workspace=None,
+                           workspace_planned: bool = False, stream=None, check: bool = True) -> int:
     a = make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, sm_scale=sm_scale,
                          chunk_tokens=chunk_tokens, max_chunks=max_chunks, part_o=part_o, part_lse=part_lse,
-                         out_o=out_o, out_lse=out_lse, kernel=kernel)
+                         out_o=out_o, out_lse=out_lse, kernel=kernel, workspace=workspace,
+                         workspace_planned=workspace_planned)
     return omni_paged_decode_attn_raw(a, stream, check)
 
 
@@ -163,6 +174,17 @@ def omni_paged_decode_attn_raw(args: omni_decode_args, stream=None, check: bool 
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_paged_decode_attn")
     return st
+
+
+def omni_decode_plan(args: omni_decode_args, stream=None, check: bool = True) -> int:
+    st = load_library().omni_decode_plan(ctypes.byref(args), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_decode_plan")
+    return st
+
+
+def omni_decode_workspace_bytes(batch: int, max_chunks: int) -> int:
+    return int(load_library().omni_decode_workspace_bytes(int(batch), int(max_chunks)))
 
 
 PartialSrc = Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor], int]

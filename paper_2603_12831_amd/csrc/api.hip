@@ -65,8 +65,32 @@ omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
     bool mfma = decode_mfma_supports(p, bf16);
     if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return OMNI_ERR_UNSUPPORTED;
     if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
-    hipError_t e = mfma ? launch_decode_mfma(p, s) : launch_decode_vector(p, bf16, s);
+    void* ws = mfma ? a->workspace : nullptr;
+    if (ws) {
+        if (a->workspace_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return OMNI_ERR_SHAPE;
+    }
+    hipError_t e = mfma ? launch_decode_mfma(p, ws, a->workspace_planned != 0, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream)
+{
+    DecodeParams p;
+    omni_status st = flatten(a, p, false);
+    if (st != OMNI_OK) return st;
+    if (!a->workspace) return OMNI_ERR_NULL;
+    if (a->workspace_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(a->workspace) % 16 != 0) return OMNI_ERR_SHAPE;
+    if (p.batch == 0) return OMNI_OK;
+    hipError_t e = launch_decode_plan(p, a->workspace, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks)
+{
+    if (batch <= 0 || max_chunks <= 0) return 0;
+    return decode_workspace_bytes(batch, max_chunks);
 }
 
 omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head_dim,

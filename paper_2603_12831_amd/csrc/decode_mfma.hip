@@ -1,13 +1,13 @@
 // Matrix-core decode attention for bf16 KV, head_dim 128, GQA ratio G <= 16.
 //
-// One workgroup of four waves per (sequence, chunk, kv head): every KV byte of
-// the chunk is read exactly once and serves all G query heads that share the
-// kv head (Eq. 1 of the paper's Background section for G queries at a time).
-// The chunk's pages are taken two at a time (a 32-token step); the steps are
-// dealt round-robin to the four waves.  Per step a wave computes, with
-// v_mfma_f32_16x16x32_bf16,
+// A work item is one (sequence, chunk, kv head): every KV byte of the chunk is
+// read exactly once and serves all G query heads that share the kv head (Eq. 1
+// of the paper's Background section for G queries at a time).  A workgroup of
+// four waves handles an item; the chunk's pages are taken two at a time (a
+// 32-token step) and the steps are dealt round-robin to the waves.  Per step a
+// wave computes, with v_mfma_f32_16x16x32_bf16,
 //
-//   S^T[token, g]  = K[token, :] . Q[g, :]         (A = K tile, B = Q^T)
+//   S^T[token, g]  = K[token, :] . Q[g, :]            (A = K tile, B = Q^T)
 //   O^T[dim, g]   += V^T[dim, token] . P^T[token, g]  (A = V^T tile, B = P^T)
 //
 // Operand layouts of the 16x16x32 instruction: lane l supplies row/col l%16
@@ -26,12 +26,23 @@
 //   * P is split into a bf16 head and a bf16 remainder (two MFMAs), which keeps
 //     the weights to ~2^-17 relative error; the products with bf16 V and the
 //     accumulation are fp32.
+//   * KV loads carry the non-temporal hint: every byte is used once.
 //
 // The online softmax works in the log2 domain (logits pre-multiplied by
 // sm_scale * log2 e), keeps one running maximum per query head (max over the
 // lane's registers, then across the four lane groups) and rescales the
 // accumulator only when some maximum of the wave moved.  The four waves'
 // states are combined through LDS with the log-sum-exp rule.
+//
+// Two launch forms share the per-step code:
+//   * grid form: one workgroup per (sequence, chunk, kv head) slot of the
+//     partial buffers, empty slots exit at once; needs no workspace.
+//   * persistent form (caller gave a workspace): a one-workgroup pass lists the
+//     non-empty (sequence, chunk) ranges longest-first and writes LSE = -inf for
+//     the empty ones; persistent workgroups then draw items from that list with
+//     an atomic ticket, and issue the first loads of their next item before the
+//     cross-wave combine of the current one, so the memory pipe never drains
+//     between items and the longest items cannot end up last.
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -44,15 +55,25 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * kWave;
 constexpr int kD = 128;
 constexpr int kPageBytes = kBlockSize * kD * 2;        // one (page, kv head) tile of K or of V
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kSortBins = 256;
 
-struct PageRegs {            // raw registers of one page: 4 KiB of K and 4 KiB of V across the wave
-    u32x4 k[4];
-    u32x4 v[4];
+struct WorkEntry { int seq, chunk, cb, ce; };          // a non-empty token range [cb, ce) of one chunk
+
+struct StepRegs {            // raw registers of one 32-token step: pages A and B, K and V, 16 KiB per wave
+    u32x4 ka[4], kb[4], va[4], vb[4];
 };
+
+struct Item {                // wave-uniform description of a work item
+    int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
+    const int* __restrict__ table;
+};
+
+struct Pages { long long a, b; };                      // physical pages of a step, -1 = absent
 
 __device__ __forceinline__ uint32_t pack_lo(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }
 __device__ __forceinline__ uint32_t pack_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
@@ -72,197 +93,188 @@ __device__ __forceinline__ void load_tile(const void* __restrict__ pool, int hkv
     const long long pg = page < 0 ? 0 : page;
     const char* src = static_cast<const char*>(pool) + (pg * hkv + kvh) * (long long)kPageBytes + lane_off;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = *reinterpret_cast<const u32x4*>(src + i * stride);
+    for (int i = 0; i < 4; ++i) r[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i * stride));
 }
 
-// physical page of logical page index `lp` (wave-uniform) if it lies in [.., lp_last] and names a pool
-// page, else -1
-__device__ __forceinline__ long long page_of(const DecodeParams& p, const int* __restrict__ table, int lp,
-                                             int lp_last)
+// physical pages of step s of an item (s wave-uniform); pages past the item's last page, or whose
+// table entry does not name a pool page, come back as -1
+__device__ __forceinline__ Pages step_pages(const DecodeParams& p, const Item& it, int s)
 {
-    lp = __builtin_amdgcn_readfirstlane(lp);
-    if (lp > lp_last) return -1;
-    long long pg = table[lp];
-    return (pg >= 0 && pg < p.num_blocks) ? pg : -1;
-}
-
-__global__ __launch_bounds__(kWaves * kWave, 2) void decode_mfma_kernel(DecodeParams p, const int* __restrict__ block_table)
-{
-    const int item = blockIdx.x;
-    const int kvh = item % p.hkv;
-    const int seq = (item / p.hkv) % p.batch;
-    const int chunk = item / (p.hkv * p.batch);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int col = lane & 15;                 // query head of the group (S^T / O^T column), or dim group for V
-    const int kg = lane >> 4;                  // k group
-    const int G = p.group;
-
-    int b, e, cb, ce;
-    seq_range(p, seq, b, e);
-    chunk_range(p, b, e, chunk, cb, ce);
-    const bool final_row = p.out_o != nullptr;                 // only set when max_chunks == 1
-    const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + (long long)kvh * G;
-    const long long orow0 = (long long)seq * p.hq + (long long)kvh * G;
-
-    if (ce <= cb) {                            // empty chunk: LSE = -inf, partial O left unwritten
-        if (threadIdx.x < G) {
-            if (p.part_lse) p.part_lse[prow0 + threadIdx.x] = -INFINITY;
-            if (final_row && p.out_lse) p.out_lse[orow0 + threadIdx.x] = -INFINITY;
-        }
-        if (final_row) {
-            for (int i = threadIdx.x; i < G * kD; i += kWaves * kWave) {
-                if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow0 * kD + i] = 0;
-                else static_cast<float*>(p.out_o)[orow0 * kD + i] = 0.f;
-            }
-        }
-        return;
+    Pages r = {-1, -1};
+    const int lp = __builtin_amdgcn_readfirstlane(it.lp_first + 2 * s);
+    if (lp <= it.lp_last) {
+        long long pg = it.table[lp];
+        r.a = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
     }
+    if (lp + 1 <= it.lp_last) {
+        long long pg = it.table[lp + 1];
+        r.b = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
+    }
+    return r;
+}
 
-    // Q^T operands: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are zero columns
-    u32x4 qb[4];
+__device__ __forceinline__ void issue_k(const DecodeParams& p, int kvh, Pages pg, int k_lane_off, StepRegs& r)
+{
+    load_tile(p.k_pool, p.hkv, pg.a, kvh, k_lane_off, 64, r.ka);        // dims i*32 + kg*8 .. of token tau
+    load_tile(p.k_pool, p.hkv, pg.b, kvh, k_lane_off, 64, r.kb);
+}
+
+__device__ __forceinline__ void issue_v(const DecodeParams& p, int kvh, Pages pg, int v_lane_off, StepRegs& r)
+{
+    load_tile(p.v_pool, p.hkv, pg.a, kvh, v_lane_off, 1024, r.va);      // token 4i + kg, dims col*8 ..
+    load_tile(p.v_pool, p.hkv, pg.b, kvh, v_lane_off, 1024, r.vb);
+}
+
+// Q^T operands: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are zero columns
+__device__ __forceinline__ void load_q(const DecodeParams& p, const Item& it, int col, int kg, u32x4 (&qb)[4])
+{
+    const u32x4 z = {0, 0, 0, 0};
+    const long long row = (long long)it.seq * p.hq + (long long)it.kvh * p.group + col;
+    const char* qp = static_cast<const char*>(p.q) + (row * kD + kg * 8) * 2;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) qb[kb] = (col < p.group) ? *reinterpret_cast<const u32x4*>(qp + kb * 64) : z;
+}
+
+__device__ __forceinline__ void finish_item(Item& it, const int* __restrict__ block_table, int max_blocks)
+{
+    it.table = block_table + (long long)it.seq * max_blocks;
+    it.lp_first = it.cb >> 4;
+    it.lp_last = (it.ce - 1) >> 4;
+    it.n_steps = (it.lp_last - it.lp_first + 2) >> 1;
+}
+
+struct WaveState {
+    f32x4 acc[8];            // acc[j][i] = O^T[dim (4*kg+i)*8 + j][head col]
+    float m_run;             // running max (log2 domain) of head `col`
+    float l_run;             // this lane's share of the running sum
+    __device__ __forceinline__ void reset()
     {
-        const u32x4 z = {0, 0, 0, 0};
-        const char* qp = static_cast<const char*>(p.q) + ((orow0 + col) * kD + kg * 8) * 2;
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) qb[kb] = (col < G) ? *reinterpret_cast<const u32x4*>(qp + kb * 64) : z;
+        for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = -INFINITY;
+        l_run = 0.f;
     }
+};
 
-    const int* __restrict__ table = block_table + (long long)seq * p.max_blocks;
-    const int lp_first = cb >> 4, lp_last = (ce - 1) >> 4;
-    const int n_steps = (lp_last - lp_first + 2) >> 1;
-    const int tau = 4 * (col & 3) + (col >> 2);            // token row this lane loads of K
-    const int k_lane_off = tau * (kD * 2) + kg * 16;
-    const int v_lane_off = lane * 16;
-    const float scale2 = p.sm_scale * kLog2e;
-
-    f32x4 acc[8];                                          // acc[j][i] = O^T[dim (4*kg+i)*8 + j][head col]
+// One 32-token step on the registers in `r`.  After K has been consumed the K tiles of the wave's next
+// step (pages `next`) are requested into the same registers, and likewise V after the PV products, when
+// `more` says there is such a step.
+__device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
+                                            const u32x4 (&qb)[4], int s, bool ok_a, bool ok_b, bool more,
+                                            Pages next, int kg, int k_lane_off, int v_lane_off, float scale2)
+{
+    // ---- S^T = K . Q^T for both pages ----------------------------------------------------------
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY;                               // running max (log2 domain) of head `col`
-    float l_run = 0.f;                                     // this lane's share of the running sum
-
-    PageRegs pa, pb;                                       // the two pages of the current step
-    int s = wave;
-    long long pgA = -1, pgB = -1;                          // physical pages of the step in registers
-    if (s < n_steps) {
-        pgA = page_of(p, table, lp_first + 2 * s, lp_last);
-        pgB = page_of(p, table, lp_first + 2 * s + 1, lp_last);
-        load_tile(p.k_pool, p.hkv, pgA, kvh, k_lane_off, 64, pa.k);      // dims i*32 + kg*8 .. of token tau
-        load_tile(p.k_pool, p.hkv, pgB, kvh, k_lane_off, 64, pb.k);
-        load_tile(p.v_pool, p.hkv, pgA, kvh, v_lane_off, 1024, pa.v);    // token 4i + kg, dims col*8 ..
-        load_tile(p.v_pool, p.hkv, pgB, kvh, v_lane_off, 1024, pb.v);
+    for (int kb = 0; kb < 4; ++kb) {
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.ka[kb]),
+                                                     __builtin_bit_cast(bf16x8, qb[kb]), sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.kb[kb]),
+                                                     __builtin_bit_cast(bf16x8, qb[kb]), sb, 0, 0, 0);
     }
-    while (s < n_steps) {
-        const int lp0 = lp_first + 2 * s;
-        const bool okA = pgA >= 0, okB = pgB >= 0;
-        const int sn = s + kWaves;
-        if (sn < n_steps) {
-            pgA = page_of(p, table, lp_first + 2 * sn, lp_last);
-            pgB = page_of(p, table, lp_first + 2 * sn + 1, lp_last);
-        }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_k(p, it.kvh, next, k_lane_off, r);
+    __builtin_amdgcn_sched_barrier(0);
 
-        // ---- S^T = K . Q^T for both pages -------------------------------------------------
-        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    // ---- logits to the log2 domain, masking on boundary steps -----------------------------------
+    const int t0 = (it.lp_first + 2 * s) << 4;             // first token of page A; register i is token 4i + kg
+    const bool interior = ok_a && ok_b && t0 >= it.cb && t0 + 32 <= it.ce;
+    uint32_t vmask[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa.k[kb]),
-                                                         __builtin_bit_cast(bf16x8, qb[kb]), sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pb.k[kb]),
-                                                         __builtin_bit_cast(bf16x8, qb[kb]), sb, 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (sn < n_steps) {                                // K registers are free again: prefetch next K
-            load_tile(p.k_pool, p.hkv, pgA, kvh, k_lane_off, 64, pa.k);
-            load_tile(p.k_pool, p.hkv, pgB, kvh, k_lane_off, 64, pb.k);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- V^T operands of this step (then the V registers are free for the prefetch) ----
-        // word j/2, half j%2 of load i holds dim (l%16)*8 + j of token 4i + kg
-        u32x4 vt[8];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            vt[2 * jj] = u32x4{pack_lo(pa.v[0][jj], pa.v[1][jj]), pack_lo(pa.v[2][jj], pa.v[3][jj]),
-                               pack_lo(pb.v[0][jj], pb.v[1][jj]), pack_lo(pb.v[2][jj], pb.v[3][jj])};
-            vt[2 * jj + 1] = u32x4{pack_hi(pa.v[0][jj], pa.v[1][jj]), pack_hi(pa.v[2][jj], pa.v[3][jj]),
-                                   pack_hi(pb.v[0][jj], pb.v[1][jj]), pack_hi(pb.v[2][jj], pb.v[3][jj])};
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (sn < n_steps) {
-            load_tile(p.v_pool, p.hkv, pgA, kvh, v_lane_off, 1024, pa.v);
-            load_tile(p.v_pool, p.hkv, pgB, kvh, v_lane_off, 1024, pb.v);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // ---- logits to the log2 domain, masking on boundary steps ---------------------------
-        const int t0 = lp0 << 4;                           // first token of page A; register i is token 4i + kg
-        const bool interior = okA && okB && t0 >= cb && t0 + 32 <= ce;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { sa[i] *= scale2; sb[i] *= scale2; }
-        if (!interior) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int ta = t0 + 4 * i + kg, tb = ta + 16;
-                const bool va = okA && ta >= cb && ta < ce;
-                const bool vb = okB && tb >= cb && tb < ce;
-                sa[i] = va ? sa[i] : -INFINITY;
-                sb[i] = vb ? sb[i] : -INFINITY;
-                // a masked token's V must not reach the MFMA (0 * NaN): V^T slot i (page A), 4+i (page B).
-                // slots 2w, 2w+1 share word w of every vt[j]
-                if (!va) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) vt[j][i >> 1] &= (i & 1) ? 0x0000ffffu : 0xffff0000u;
-                }
-                if (!vb) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) vt[j][2 + (i >> 1)] &= (i & 1) ? 0x0000ffffu : 0xffff0000u;
-                }
-            }
-        }
-        // ---- online softmax ------------------------------------------------------------------
-        float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])),
-                         fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;      // nothing seen yet: avoid inf - inf
-        if (__any(m_new > m_run)) {
-            const float corr = __builtin_amdgcn_exp2f(m_run - m_use);   // 0 when m_run = -inf
-            l_run *= corr;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] *= corr;
-        }
-        m_run = m_new;
-        float pw[8];
+    for (int i = 0; i < 4; ++i) { sa[i] *= scale2; sb[i] *= scale2; }
+    if (!interior) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            pw[i] = __builtin_amdgcn_exp2f(sa[i] - m_use);
-            pw[4 + i] = __builtin_amdgcn_exp2f(sb[i] - m_use);
+            const int ta = t0 + 4 * i + kg, tb = ta + 16;
+            const bool va = ok_a && ta >= it.cb && ta < it.ce;
+            const bool vb = ok_b && tb >= it.cb && tb < it.ce;
+            sa[i] = va ? sa[i] : -INFINITY;
+            sb[i] = vb ? sb[i] : -INFINITY;
+            // a masked token's V must not reach the MFMA (0 * NaN): V^T k-slot i (page A) or 4+i (page B);
+            // slots 2w, 2w+1 are the two halves of operand word w
+            const uint32_t keep = (i & 1) ? 0x0000ffffu : 0xffff0000u;
+            if (!va) vmask[i >> 1] &= keep;
+            if (!vb) vmask[2 + (i >> 1)] &= keep;
         }
-        l_run += ((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7]));
-        // P^T operand: bf16 head and bf16 remainder of every weight
-        u32x4 ph, pl;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const uint32_t h = pack_bf16(pw[2 * w], pw[2 * w + 1]);
-            ph[w] = h;
-            pl[w] = pack_bf16(pw[2 * w] - bf16lo_to_f32(h), pw[2 * w + 1] - bf16hi_to_f32(h));
-        }
-        // ---- O^T += V^T . P^T ------------------------------------------------------------------
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[j]),
-                                                             __builtin_bit_cast(bf16x8, ph), acc[j], 0, 0, 0);
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[j]),
-                                                             __builtin_bit_cast(bf16x8, pl), acc[j], 0, 0, 0);
-        }
-        s = sn;
     }
+    // ---- online softmax ----------------------------------------------------------------------------
+    float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st.m_run, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // nothing seen yet: avoid inf - inf
+    if (__any(m_new > st.m_run)) {
+        const float corr = __builtin_amdgcn_exp2f(st.m_run - m_use);   // 0 when m_run = -inf
+        st.l_run *= corr;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[j] *= corr;
+    }
+    st.m_run = m_new;
+    float pw[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        pw[i] = __builtin_amdgcn_exp2f(sa[i] - m_use);
+        pw[4 + i] = __builtin_amdgcn_exp2f(sb[i] - m_use);
+    }
+    st.l_run += ((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7]));
+    // P^T operand: bf16 head and bf16 remainder of every weight
+    u32x4 ph, pl;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t h = pack_bf16(pw[2 * w], pw[2 * w + 1]);
+        ph[w] = h;
+        pl[w] = pack_bf16(pw[2 * w] - bf16lo_to_f32(h), pw[2 * w + 1] - bf16hi_to_f32(h));
+    }
+    // ---- O^T += V^T . P^T: word j/2, half j%2 of load i holds dim (l%16)*8 + j of token 4i + kg ----
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        u32x4 lo = {pack_lo(r.va[0][jj], r.va[1][jj]), pack_lo(r.va[2][jj], r.va[3][jj]),
+                    pack_lo(r.vb[0][jj], r.vb[1][jj]), pack_lo(r.vb[2][jj], r.vb[3][jj])};
+        u32x4 hi = {pack_hi(r.va[0][jj], r.va[1][jj]), pack_hi(r.va[2][jj], r.va[3][jj]),
+                    pack_hi(r.vb[0][jj], r.vb[1][jj]), pack_hi(r.vb[2][jj], r.vb[3][jj])};
+        if (!interior) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { lo[w] &= vmask[w]; hi[w] &= vmask[w]; }
+        }
+        f32x4 a0 = st.acc[2 * jj], a1 = st.acc[2 * jj + 1];
+        a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), __builtin_bit_cast(bf16x8, ph), a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), __builtin_bit_cast(bf16x8, ph), a1, 0, 0, 0);
+        a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), __builtin_bit_cast(bf16x8, pl), a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), __builtin_bit_cast(bf16x8, pl), a1, 0, 0, 0);
+        st.acc[2 * jj] = a0;
+        st.acc[2 * jj + 1] = a1;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) issue_v(p, it.kvh, next, v_lane_off, r);
+    __builtin_amdgcn_sched_barrier(0);
+}
 
-    // ---- combine the four waves ------------------------------------------------------------------
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    extern __shared__ float lds[];                         // [kWaves][G][kD] accumulators, then m and l
+// All steps of an item that belong to this wave.  On entry the registers of the wave's first step are
+// already requested (if it has one).
+__device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
+                                         const u32x4 (&qb)[4], int wave, int kg, int k_lane_off, int v_lane_off,
+                                         float scale2, Pages cur)
+{
+    int s = wave;
+    Pages nxt = {-1, -1};
+    if (s + kWaves < it.n_steps) nxt = step_pages(p, it, s + kWaves);
+    while (s < it.n_steps) {
+        const bool more = s + kWaves < it.n_steps;
+        Pages nn = {-1, -1};
+        if (s + 2 * kWaves < it.n_steps) nn = step_pages(p, it, s + 2 * kWaves);   // table reads run a step ahead
+        attend_step(p, it, st, r, qb, s, cur.a >= 0, cur.b >= 0, more, nxt, kg, k_lane_off, v_lane_off, scale2);
+        cur = nxt;
+        nxt = nn;
+        s += kWaves;
+    }
+}
+
+// LDS layout of the cross-wave combine: [kWaves][G][kD] accumulators, then [kWaves][16] m and l.
+__device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds, int G, int wave, int col, int kg)
+{
+    float l = st.l_run;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
     float* sh_acc = lds;
     float* sh_m = lds + kWaves * G * kD;
     float* sh_l = sh_m + kWaves * 16;
@@ -271,11 +283,21 @@ __global__ __launch_bounds__(kWaves * kWave, 2) void decode_mfma_kernel(DecodePa
 #pragma unroll
         for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dst[(4 * kg + i) * 8 + j] = acc[j][i];
-        if (kg == 0) { sh_m[wave * 16 + col] = m_run; sh_l[wave * 16 + col] = l_run; }
+            for (int i = 0; i < 4; ++i) dst[(4 * kg + i) * 8 + j] = st.acc[j][i];
+        if (kg == 0) { sh_m[wave * 16 + col] = st.m_run; sh_l[wave * 16 + col] = l; }
     }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < G * kD; idx += kWaves * kWave) {
+}
+
+// after a barrier: merge the waves' states with the log-sum-exp rule and write the item's rows
+__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G)
+{
+    const float* sh_acc = lds;
+    const float* sh_m = lds + kWaves * G * kD;
+    const float* sh_l = sh_m + kWaves * 16;
+    const bool final_row = p.out_o != nullptr;                 // only set when max_chunks == 1
+    const long long prow0 = ((long long)it.seq * p.max_chunks + it.chunk) * p.hq + (long long)it.kvh * G;
+    const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
+    for (int idx = threadIdx.x; idx < G * kD; idx += kThreads) {
         const int g = idx >> 7, d = idx & (kD - 1);
         float mm = -INFINITY;
 #pragma unroll
@@ -303,6 +325,307 @@ __global__ __launch_bounds__(kWaves * kWave, 2) void decode_mfma_kernel(DecodePa
     }
 }
 
+// rows of an empty range: LSE = -inf, final O = 0, partial O left unwritten; `heads` rows from `head0`
+__device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int chunk, int head0, int heads,
+                                            int tid, int nthreads)
+{
+    const bool final_row = p.out_o != nullptr;
+    const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + head0;
+    const long long orow0 = (long long)seq * p.hq + head0;
+    for (int h = tid; h < heads; h += nthreads) {
+        if (p.part_lse) p.part_lse[prow0 + h] = -INFINITY;
+        if (final_row && p.out_lse) p.out_lse[orow0 + h] = -INFINITY;
+    }
+    if (final_row) {
+        for (int i = tid; i < heads * kD; i += nthreads) {
+            if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow0 * kD + i] = 0;
+            else static_cast<float*>(p.out_o)[orow0 * kD + i] = 0.f;
+        }
+    }
+}
+
+struct LaneIds {
+    int lane, wave, col, kg, k_lane_off, v_lane_off;
+    __device__ __forceinline__ LaneIds()
+    {
+        lane = threadIdx.x & 63;
+        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        col = lane & 15;                                   // head column of S^T / O^T, dim group of V
+        kg = lane >> 4;                                    // k group
+        const int tau = 4 * (col & 3) + (col >> 2);        // token row this lane loads of K
+        k_lane_off = tau * (kD * 2) + kg * 16;
+        v_lane_off = lane * 16;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------------
+// grid form
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodeParams p, const int* __restrict__ block_table)
+{
+    extern __shared__ float lds[];
+    const LaneIds id;
+    Item it;
+    const int item = blockIdx.x;
+    it.kvh = item % p.hkv;
+    it.seq = (item / p.hkv) % p.batch;
+    it.chunk = item / (p.hkv * p.batch);
+    int b, e;
+    seq_range(p, it.seq, b, e);
+    chunk_range(p, b, e, it.chunk, it.cb, it.ce);
+    if (it.ce <= it.cb) {
+        store_empty(p, it.seq, it.chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads);
+        return;
+    }
+    finish_item(it, block_table, p.max_blocks);
+    const float scale2 = p.sm_scale * kLog2e;
+    u32x4 qb[4];
+    load_q(p, it, id.col, id.kg, qb);
+    WaveState st;
+    st.reset();
+    StepRegs r;
+    Pages cur = {-1, -1};
+    if (id.wave < it.n_steps) {
+        cur = step_pages(p, it, id.wave);
+        issue_k(p, it.kvh, cur, id.k_lane_off, r);
+        issue_v(p, it.kvh, cur, id.v_lane_off, r);
+    }
+    run_item(p, it, st, r, qb, id.wave, id.kg, id.k_lane_off, id.v_lane_off, scale2, cur);
+    stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
+    __syncthreads();
+    combine_and_store(p, it, lds, p.group);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// persistent form
+// ---------------------------------------------------------------------------------------------------
+// Workspace: 16 words of header (see decode_list_kernel), then batch * max_chunks entries.
+constexpr int kHeaderWords = 16;
+
+__device__ __forceinline__ int sort_bin(int tokens, float bins_per_page)
+{
+    const int pages = (tokens + kBlockSize - 1) / kBlockSize;
+    int b = (int)((float)pages * bins_per_page);
+    if (b > kSortBins - 1) b = kSortBins - 1;
+    return (kSortBins - 1) - b;                            // bin 0 holds the longest ranges
+}
+
+// Wave-aggregated counter: every active lane adds one to counters[key]; lanes with equal keys are served
+// by a single LDS atomic.  Returns the lane's own slot (old value + rank among the lanes sharing its key).
+// Must be called by all lanes of the wave together.
+__device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, bool active)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned slot = 0;
+    unsigned long long todo = __ballot(active);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int k = __shfl(key, leader);
+        const bool mine = active && key == k;
+        const unsigned long long grp = __ballot(mine);
+        unsigned base = 0;
+        if (lane == leader) base = atomicAdd(&counters[k], (unsigned)__popcll(grp));
+        base = __shfl(base, leader);
+        if (mine) slot = base + (unsigned)__popcll(grp & ((1ull << lane) - 1ull));
+        todo &= ~grp;
+    }
+    return slot;
+}
+
+// Work list of a call: the non-empty (sequence, chunk) ranges, longest first, from the front of
+// `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
+// of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here).  Depends only on the ranges and the chunking, so a
+// list can serve every call that shares them (all layers of one decoding iteration).
+__global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsigned* __restrict__ header,
+                                                           WorkEntry* __restrict__ entries)
+{
+    __shared__ unsigned hist[kSortBins + 1];               // last counter: empty entries
+    const int total = p.batch * p.max_chunks;
+    const int max_pages = p.chunk_tokens / kBlockSize > 0 ? p.chunk_tokens / kBlockSize : 1;
+    const float bins_per_page = (float)(kSortBins - 1) / (float)max_pages;
+    for (int i = threadIdx.x; i < kSortBins + 1; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    for (int base = 0; base < total; base += blockDim.x) {
+        const int e = base + threadIdx.x;
+        int cb = 0, ce = 0;
+        if (e < total) {
+            int b, en;
+            seq_range(p, e / p.max_chunks, b, en);
+            chunk_range(p, b, en, e % p.max_chunks, cb, ce);
+        }
+        const bool live = ce > cb;
+        wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) {                             // exclusive scan by one wave: bin -> first output slot
+        constexpr int kPer = kSortBins / kWave;
+        unsigned c[kPer], sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) { c[i] = hist[threadIdx.x * kPer + i]; sum += c[i]; }
+        unsigned incl = sum;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const unsigned up = __shfl_up(incl, d);
+            if ((int)threadIdx.x >= d) incl += up;
+        }
+        unsigned run = incl - sum;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) { hist[threadIdx.x * kPer + i] = run; run += c[i]; }
+        if (threadIdx.x == kWave - 1) {
+            header[0] = 0;
+            header[1] = incl;
+            header[2] = hist[kSortBins];
+            header[3] = 0;
+            hist[kSortBins] = 0;
+        }
+    }
+    __syncthreads();
+    for (int base = 0; base < total; base += blockDim.x) {
+        const int e = base + threadIdx.x;
+        int cb = 0, ce = 0, seq = 0, chunk = 0;
+        if (e < total) {
+            int b, en;
+            seq = e / p.max_chunks;
+            chunk = e % p.max_chunks;
+            seq_range(p, seq, b, en);
+            chunk_range(p, b, en, chunk, cb, ce);
+        }
+        const bool live = ce > cb;
+        const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total);
+        if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, chunk, cb, ce};
+    }
+}
+
+__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
+                                            const int* __restrict__ block_table, unsigned ticket)
+{
+    const WorkEntry w = entries[ticket / (unsigned)p.hkv];
+    Item it;
+    it.kvh = (int)(ticket % (unsigned)p.hkv);
+    it.seq = w.seq; it.chunk = w.chunk; it.cb = w.cb; it.ce = w.ce;
+    finish_item(it, block_table, p.max_blocks);
+    return it;
+}
+
+#ifndef OMNI_P_OCC
+#define OMNI_P_OCC 2
+#endif
+#ifndef OMNI_P_HOIST
+#define OMNI_P_HOIST 1
+#endif
+#ifndef OMNI_P_STAGE_FIRST
+#define OMNI_P_STAGE_FIRST 1
+#endif
+__device__ __forceinline__ void persistent_body(
+    const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
+    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
+{
+    extern __shared__ float lds[];
+    __shared__ unsigned sh_ticket[3];
+    const LaneIds id;
+    const unsigned n_tickets = counts[0] * (unsigned)p.hkv;
+    const float scale2 = p.sm_scale * kLog2e;
+
+    // rows of empty chunks: LSE = -inf (stores only, shared out over the resident workgroups)
+    {
+        const unsigned n_empty = counts[1];
+        const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
+        for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
+            const WorkEntry w = entries[last - i];
+            store_empty(p, w.seq, w.chunk, 0, p.hq, threadIdx.x, kThreads);
+        }
+    }
+
+    if (threadIdx.x == 0) {                                // the workgroup's first two tickets
+        const unsigned t = atomicAdd(ticket_counter, 2u);
+        sh_ticket[0] = t;
+        sh_ticket[1] = t + 1;
+    }
+    __syncthreads();
+    unsigned tk = __builtin_amdgcn_readfirstlane(sh_ticket[0]);
+    if (tk >= n_tickets) return;
+
+    Item it = ticket_item(p, entries, block_table, tk);
+    u32x4 qb[4];
+    load_q(p, it, id.col, id.kg, qb);
+    WaveState st;
+    st.reset();
+    StepRegs r;
+    Pages cur = {-1, -1};
+    if (id.wave < it.n_steps) {
+        cur = step_pages(p, it, id.wave);
+        issue_k(p, it.kvh, cur, id.k_lane_off, r);
+        issue_v(p, it.kvh, cur, id.v_lane_off, r);
+    }
+    for (int k = 0;; ++k) {
+        unsigned t2 = 0;                                   // ticket of the item after next, drawn early
+        if (threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
+
+        // the next item's description and first pages are fetched while this item streams
+        const unsigned tn = __builtin_amdgcn_readfirstlane(sh_ticket[(k + 1) % 3]);
+        const bool has_next = tn < n_tickets;
+        Item nx = it;
+        Pages nx_first = {-1, -1};
+#if OMNI_P_HOIST
+        if (has_next) {
+            nx = ticket_item(p, entries, block_table, tn);
+            if (id.wave < nx.n_steps) nx_first = step_pages(p, nx, id.wave);
+        }
+#endif
+
+        run_item(p, it, st, r, qb, id.wave, id.kg, id.k_lane_off, id.v_lane_off, scale2, cur);
+
+#if !OMNI_P_HOIST
+        if (has_next) {
+            nx = ticket_item(p, entries, block_table, tn);
+            if (id.wave < nx.n_steps) nx_first = step_pages(p, nx, id.wave);
+        }
+#endif
+
+        // accumulators go to LDS, then the next item's Q and first step are requested, and only then the
+        // workgroup meets for the combine: the loads fly during both barriers
+#if OMNI_P_STAGE_FIRST
+        stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
+#endif
+        if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
+        if (has_next) {
+            load_q(p, nx, id.col, id.kg, qb);
+            cur = nx_first;
+            if (id.wave < nx.n_steps) {
+                issue_k(p, nx.kvh, cur, id.k_lane_off, r);
+                issue_v(p, nx.kvh, cur, id.v_lane_off, r);
+            }
+        }
+#if !OMNI_P_STAGE_FIRST
+        stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
+#endif
+        __syncthreads();
+        combine_and_store(p, it, lds, p.group);
+        if (!has_next) break;
+        __syncthreads();                                   // LDS is rewritten by the next item's staging
+        st.reset();
+        it = nx;
+    }
+}
+
+// Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
+// list; the last workgroup to leave puts both back to zero, so the same list can serve the next call.
+__global__ __launch_bounds__(kThreads, OMNI_P_OCC) void decode_mfma_persistent_kernel(
+    DecodeParams p, const int* __restrict__ block_table, unsigned* header,
+    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
+{
+    persistent_body(p, block_table, header, counts, entries);
+    if (threadIdx.x == 0) {
+        const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
+        if (gone == gridDim.x - 1) {
+            atomicExch(header + 3, 0u);
+            atomicExch(header, 0u);
+        }
+    }
+}
+
+size_t lds_bytes(int group) { return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float); }
+
 }  // namespace
 
 bool decode_mfma_supports(const DecodeParams& p, bool bf16)
@@ -311,11 +634,42 @@ bool decode_mfma_supports(const DecodeParams& p, bool bf16)
            (long long)p.batch * p.max_chunks * p.hkv <= 0x7fffffffLL;
 }
 
-hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t s)
+size_t decode_workspace_bytes(long long batch, long long max_chunks)
 {
-    const unsigned grid = (unsigned)((long long)p.batch * p.max_chunks * p.hkv);
-    const size_t lds = (size_t)(kWaves * p.group * kD + 2 * kWaves * 16) * sizeof(float);
-    hipLaunchKernelGGL(decode_mfma_kernel, dim3(grid), dim3(kWaves * kWave), lds, s, p, p.block_table);
+    return (size_t)kHeaderWords * sizeof(unsigned) + (size_t)(batch * max_chunks) * sizeof(WorkEntry);
+}
+
+hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s)
+{
+    unsigned* header = static_cast<unsigned*>(workspace);
+    WorkEntry* entries = reinterpret_cast<WorkEntry*>(header + kHeaderWords);
+    hipLaunchKernelGGL(decode_list_kernel, dim3(1), dim3(1024), 0, s, p, header, entries);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s)
+{
+    if (!workspace) {
+        const unsigned grid = (unsigned)((long long)p.batch * p.max_chunks * p.hkv);
+        hipLaunchKernelGGL(decode_mfma_grid_kernel, dim3(grid), dim3(kThreads), lds_bytes(p.group), s, p, p.block_table);
+        return hipGetLastError();
+    }
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    unsigned* header = static_cast<unsigned*>(workspace);
+    WorkEntry* entries = reinterpret_cast<WorkEntry*>(header + kHeaderWords);
+    if (!planned) {
+        e = launch_decode_plan(p, workspace, s);
+        if (e != hipSuccess) return e;
+    }
+    // more workgroups than can be resident are harmless: late ones find the tickets gone
+    long long want = (long long)cus * 4, cap = (long long)p.batch * p.max_chunks * p.hkv;
+    const unsigned grid = (unsigned)(want < cap ? want : cap);
+    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds_bytes(p.group), s, p,
+                       p.block_table, header, header + 1, entries);
     return hipGetLastError();
 }
 

@@ -75,7 +75,9 @@ __device__ __forceinline__ void chunk_range(const DecodeParams& p, int b, int e,
 
 // ---- launchers (each defined beside its kernel) ---------------------------
 hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
-hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t s);
+hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s);
+hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s);
+size_t decode_workspace_bytes(long long batch, long long max_chunks);
 bool decode_mfma_supports(const DecodeParams& p, bool bf16);
 hipError_t launch_merge(const MergeParams& p, hipStream_t s);
 hipError_t launch_gather(const DecodeParams& p, bool bf16, int seq, void* k_out, void* v_out, hipStream_t s);

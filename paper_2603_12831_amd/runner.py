@@ -24,7 +24,7 @@ class DeviceWorkload:
 
     def __init__(self, w: Workload, device="cuda:0", out_dtype: Optional[str] = None,
                  ext_o: Optional[np.ndarray] = None, ext_lse: Optional[np.ndarray] = None,
-                 ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1):
+                 ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1, workspace: bool = True):
         self.w = w
         self.device = torch.device(device)
         k_pool, v_pool, table = w.device_views()
@@ -41,7 +41,9 @@ class DeviceWorkload:
                 end=torch.from_numpy(np.ascontiguousarray(c.ctx_end, dtype=np.int32)).to(self.device),
                 chunk_tokens=c.chunk_tokens, max_chunks=c.max_chunks,
                 part_o=torch.empty((B, c.max_chunks, Hq, D), dtype=torch.float32, device=self.device),
-                part_lse=torch.empty((B, c.max_chunks, Hq), dtype=torch.float32, device=self.device)))
+                part_lse=torch.empty((B, c.max_chunks, Hq), dtype=torch.float32, device=self.device),
+                workspace=torch.empty(binding.omni_decode_workspace_bytes(B, c.max_chunks), dtype=torch.uint8,
+                                      device=self.device) if workspace else None))
         self.ext = None
         if ext_o is not None:
             self.ext = (torch.from_numpy(np.ascontiguousarray(ext_o, dtype=np.float32)).to(self.device),
@@ -62,15 +64,34 @@ class DeviceWorkload:
         self.out_o.fill_(float("nan"))
         self.out_lse.fill_(float("nan"))
 
-    def run_attention(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
+    def decode_args(self, c, kernel: int, pool: int, planned: bool):
+        return binding.make_decode_args(
+            self.q, self.k_pools[pool], self.v_pools[pool], self.block_table, c["begin"], c["end"],
+            sm_scale=self.w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
+            part_o=None if self.direct else c["part_o"], part_lse=None if self.direct else c["part_lse"],
+            out_o=self.out_o if self.direct else None, out_lse=self.out_lse if self.direct else None,
+            kernel=kernel, workspace=c["workspace"], workspace_planned=planned)
+
+    def plan(self, stream=None):
+        """Build the work list of every decode call once (it can then serve many attention passes)."""
+        for c in self.calls:
+            if c["workspace"] is not None:
+                binding.omni_decode_plan(self.decode_args(c, binding.OMNI_KERNEL_AUTO, 0, False), stream)
+
+    def run_attention(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None,
+                      planned: bool = False):
         w = self.w
+        if planned:
+            for c in self.calls:
+                binding.omni_paged_decode_attn_raw(self.decode_args(c, kernel, pool, True), stream)
+            return
         for c in self.calls:
             binding.omni_paged_decode_attn(
                 self.q, self.k_pools[pool], self.v_pools[pool], self.block_table, c["begin"], c["end"],
                 sm_scale=w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
                 part_o=None if self.direct else c["part_o"], part_lse=None if self.direct else c["part_lse"],
                 out_o=self.out_o if self.direct else None, out_lse=self.out_lse if self.direct else None,
-                kernel=kernel, stream=stream)
+                kernel=kernel, workspace=c["workspace"], stream=stream)
 
     def merge_sources(self) -> List:
         srcs = [self.ext] if self.ext is not None else []

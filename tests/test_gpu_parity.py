@@ -23,7 +23,12 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-3}
 THREADS = 16
-KERNELS = [binding.OMNI_KERNEL_VECTOR, binding.OMNI_KERNEL_AUTO]
+# (kernel selector, give a workspace): the vector kernel, and both launch forms of the automatic choice
+# (which is the matrix-core kernel for bf16 / head_dim 128 and the vector kernel otherwise)
+KERNELS = [pytest.param((binding.OMNI_KERNEL_VECTOR, False), id="vector"),
+           pytest.param((binding.OMNI_KERNEL_AUTO, False), id="auto-grid"),
+           pytest.param((binding.OMNI_KERNEL_AUTO, True), id="auto-persistent")]
+BENCH_FORM = (binding.OMNI_KERNEL_AUTO, True)          # what bench.py times
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -77,9 +82,10 @@ def check(got_o, got_l, exp_o, exp_l, tol, what=""):
 
 def run_and_check(w, kernel, out_dtype="f32", tol=None, ext=None, expected=None):
     ext = ext or (None, None, None)
-    dw = DeviceWorkload(w, out_dtype=out_dtype, ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2])
+    dw = DeviceWorkload(w, out_dtype=out_dtype, ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2],
+                        workspace=kernel[1])
     dw.poison_outputs()
-    dw.run(kernel=kernel)
+    dw.run(kernel=kernel[0])
     got_o, got_l = dw.results()
     exp_o, exp_l = expected if expected is not None else expected_full(w)
     return check(got_o, got_l, exp_o, exp_l, tol or TOL[w.dtype], w.name), dw
@@ -172,9 +178,9 @@ def test_empty_and_reversed_ranges_give_zero_and_minus_inf(kernel):
     w.calls[0].ctx_end = np.array([0, 40, 10], dtype=np.int32)
     for chunk, mc in [(0, 1), (16, 4)]:
         w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, mc
-        dw = DeviceWorkload(w, out_dtype="f32")
+        dw = DeviceWorkload(w, out_dtype="f32", workspace=kernel[1])
         dw.poison_outputs()
-        dw.run(kernel=kernel)
+        dw.run(kernel=kernel[0])
         o, l = dw.results()
         assert np.all(o == 0) and np.all(l == -np.inf)
 
@@ -270,8 +276,8 @@ def test_index_revealing_attention_is_exact(kernel, dtype):
             v[w.block_table[i, t // 16], :, t % 16, :] = (t % 64) + (i % 2)          # <= 64: exact in bf16
     w.q = q if dtype == "f32" else wl.f32_to_bf16_bits(q)
     w.v_pool = v if dtype == "f32" else wl.f32_to_bf16_bits(v)
-    dw = DeviceWorkload(w, out_dtype="f32")
-    dw.run(kernel=kernel)
+    dw = DeviceWorkload(w, out_dtype="f32", workspace=kernel[1])
+    dw.run(kernel=kernel[0])
     o, lse = dw.results()
     for i, L in enumerate(lengths):
         n = L - int(begins[i])
@@ -284,11 +290,11 @@ def test_index_revealing_attention_is_exact(kernel, dtype):
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_deterministic_and_placement_independent(kernel):
     w = wl.make_cfg3(batch=8, median=400, lo=10, hi=1500, chunk_tokens=256)
-    dw = DeviceWorkload(w, out_dtype="f32")
-    dw.run(kernel=kernel)
+    dw = DeviceWorkload(w, out_dtype="f32", workspace=kernel[1])
+    dw.run(kernel=kernel[0])
     o1, l1 = dw.results()
     dw.poison_outputs()
-    dw.run(kernel=kernel)
+    dw.run(kernel=kernel[0])
     o2, l2 = dw.results()
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
     # move every page to a new physical home, table updated: bit-identical outputs
@@ -297,10 +303,43 @@ def test_deterministic_and_placement_independent(kernel):
     k2[perm], v2[perm] = w.k_pool, w.v_pool
     w.k_pool, w.v_pool = k2, v2
     w.block_table = np.where(w.block_table >= 0, perm[np.maximum(w.block_table, 0)], -1).astype(np.int32)
-    dw3 = DeviceWorkload(w, out_dtype="f32")
-    dw3.run(kernel=kernel)
+    dw3 = DeviceWorkload(w, out_dtype="f32", workspace=kernel[1])
+    dw3.run(kernel=kernel[0])
     o3, l3 = dw3.results()
     assert np.array_equal(o1, o3) and np.array_equal(l1, l3)
+
+
+def test_plan_once_serves_many_passes():
+    """One work list (omni_decode_plan) reused by several attention passes over the same ranges,
+    as the layers of one decoding iteration would: results equal the self-planning call bit for bit."""
+    w = wl.make_cfg3(batch=24, median=500, lo=1, hi=3000, chunk_tokens=512)
+    w.calls[0].ctx_end[3] = 0                                   # an empty sequence among them
+    ref = DeviceWorkload(w, out_dtype="f32")
+    ref.run()
+    o_ref, l_ref = ref.results()
+    check(o_ref, l_ref, *expected_full(w), 2e-3, "self-planned")
+    dw = DeviceWorkload(w, out_dtype="f32")
+    dw.plan()
+    for layer in range(3):
+        dw.poison_outputs()
+        dw.run_attention(planned=True)
+        dw.run_merge()
+        o, l = dw.results()
+        assert np.array_equal(o, o_ref) and np.array_equal(l, l_ref)
+    # another "layer": different q and KV, same ranges, same plan
+    w2 = wl.make_cfg3(batch=24, median=500, lo=1, hi=3000, chunk_tokens=512)
+    w2.calls = w.calls
+    w2.q = wl._normal(w.q.shape, [77, 1], 1.0, "bf16")
+    w2.k_pool = wl._normal(w.k_pool.shape, [77, 2], 1.0, "bf16")
+    w2.v_pool = wl._normal(w.v_pool.shape, [77, 3], 1.0, "bf16")
+    dw.q.copy_(to_device(w2.q, "bf16", dw.device))
+    dw.k_pools[0].copy_(to_device(w2.k_pool, "bf16", dw.device))
+    dw.v_pools[0].copy_(to_device(w2.v_pool, "bf16", dw.device))
+    dw.poison_outputs()
+    dw.run_attention(planned=True)
+    dw.run_merge()
+    o, l = dw.results()
+    check(o, l, *expected_full(w2), 2e-3, "second layer on a reused plan")
 
 
 # ---------------------------------------------------------------------------
@@ -360,25 +399,27 @@ def test_merge_random_sources(d, out_dtype):
 # ---------------------------------------------------------------------------
 def test_full_cfg2():
     w = wl.make_cfg2(workers=THREADS)
-    (eo, el), _ = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="bf16")
+    (eo, el), _ = run_and_check(w, BENCH_FORM, out_dtype="bf16")
     print("cfg2 max abs err O %.3g LSE %.3g" % (eo, el))
 
 
 def test_full_cfg3():
     w = wl.make_cfg3(workers=THREADS)
-    (eo, el), dw = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="f32")
+    (eo, el), dw = run_and_check(w, BENCH_FORM, out_dtype="f32")
     print("cfg3 max abs err O %.3g LSE %.3g" % (eo, el))
     # the bf16 output the config asks for is the correctly rounded fp32 result, up to one step
     exp_o, _ = expected_full(w)
     dwb = DeviceWorkload(w, out_dtype="bf16")
     dwb.run()
+    # the grid form on the full size too
+    run_and_check(w, (binding.OMNI_KERNEL_AUTO, False), out_dtype="f32")
     ob, _ = dwb.results()
     assert np.max(np.abs(ob - exp_o) / np.maximum(np.abs(exp_o), 2.0 ** -6)) <= 2.0 ** -8 + 1e-3
 
 
 def test_full_cfg4():
     w = wl.make_cfg4(workers=THREADS)
-    (eo, el), _ = run_and_check(w, binding.OMNI_KERNEL_AUTO, out_dtype="f32", ext=ext_partials_from_oracle(w))
+    (eo, el), _ = run_and_check(w, BENCH_FORM, out_dtype="f32", ext=ext_partials_from_oracle(w))
     print("cfg4 max abs err O %.3g LSE %.3g" % (eo, el))
 
 

@@ -64,6 +64,18 @@ def test_decode_argument_errors(over, code):
     assert lib.omni_paged_decode_attn(None, None) == binding.OMNI_ERR_NULL
 
 
+def test_plan_argument_errors_and_workspace_size():
+    lib = binding.load_library()
+    assert lib.omni_decode_workspace_bytes(256, 8) >= 16 * 256 * 8
+    assert lib.omni_decode_workspace_bytes(0, 8) == 0 and lib.omni_decode_workspace_bytes(4, -1) == 0
+    assert lib.omni_decode_plan(None, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_decode_plan(ctypes.byref(_args()), None) == binding.OMNI_ERR_NULL        # no workspace
+    assert lib.omni_decode_plan(ctypes.byref(_args(workspace=0x1000, workspace_bytes=8)), None) == binding.OMNI_ERR_SHAPE
+    assert lib.omni_decode_plan(ctypes.byref(_args(workspace=0x1008, workspace_bytes=1 << 20)), None) == binding.OMNI_ERR_SHAPE
+    assert lib.omni_decode_plan(ctypes.byref(_args(workspace=0x1000, workspace_bytes=1 << 20, chunk_tokens=8,
+                                                   max_chunks=2)), None) == binding.OMNI_ERR_SHAPE
+
+
 def test_merge_and_aid_argument_errors():
     lib = binding.load_library()
     src = (binding.omni_partial_src * 1)()
