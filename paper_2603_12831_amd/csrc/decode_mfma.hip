@@ -64,9 +64,17 @@ constexpr int kSortBins = 256;
 
 struct WorkEntry { int seq, chunk, cb, ce; };          // a non-empty token range [cb, ce) of one chunk
 
-struct StepRegs {            // raw registers of one 32-token step: pages A and B, K and V, 16 KiB per wave
-    u32x4 ka[4], kb[4], va[4], vb[4];
+struct StepRegs {            // raw V registers of one 32-token step (pages A and B); K waits in LDS
+    u32x4 va[4], vb[4];
 };
+
+constexpr int kStageBytes = 2 * kPageBytes;            // per-wave LDS staging of a step's two K tiles
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+// wait until at most n vector-memory operations of this wave are outstanding (they retire in order)
+#define OMNI_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) >> 4) << 14) | 0x0F70 | ((n) & 0xF))
 
 struct Item {                // wave-uniform description of a work item
     int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
@@ -113,10 +121,34 @@ __device__ __forceinline__ Pages step_pages(const DecodeParams& p, const Item& i
     return r;
 }
 
-__device__ __forceinline__ void issue_k(const DecodeParams& p, int kvh, Pages pg, int k_lane_off, StepRegs& r)
+// K tiles of a step go from HBM straight into the wave's LDS staging area (no registers while in
+// flight).  A wave-wide 16-byte direct load puts lane s's data at base + 16 s, so for KiB i of a page
+// lane s fetches token 4i + s/16, 16-byte chunk (s%16) ^ token: the global side stays whole 256-byte
+// rows per 16 lanes, and the LDS image is XOR-swizzled so that the later operand reads (16 lanes =
+// 16 different tokens, same chunk) touch every bank once.  An absent page reads page 0 (masked later).
+__device__ __forceinline__ void issue_k(const DecodeParams& p, int kvh, Pages pg, int lane, char* stage)
 {
-    load_tile(p.k_pool, p.hkv, pg.a, kvh, k_lane_off, 64, r.ka);        // dims i*32 + kg*8 .. of token tau
-    load_tile(p.k_pool, p.hkv, pg.b, kvh, k_lane_off, 64, r.kb);
+    const int row = lane >> 4, chunk = lane & 15;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const long long page = half ? pg.b : pg.a;
+        const long long pgc = page < 0 ? 0 : page;
+        const char* src = static_cast<const char*>(p.k_pool) + (pgc * p.hkv + kvh) * (long long)kPageBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = 4 * i + row;
+            const char* g = src + tok * (kD * 2) + ((chunk ^ tok) & 15) * 16;
+            __builtin_amdgcn_global_load_lds((global_void*)g, (lds_void*)(stage + half * kPageBytes + i * 1024), 16, 0, 0);
+        }
+    }
+}
+
+// operand kb of page `half` for the S^T product: lane (row r = l%16, k group kg) needs token tau(r),
+// 16-byte chunk kb*4 + kg, found at the swizzled position written by issue_k
+__device__ __forceinline__ u32x4 read_k(const char* stage, int half, int kb, int tau, int kg)
+{
+    const int chunk = kb * 4 + kg;
+    return *reinterpret_cast<const u32x4*>(stage + half * kPageBytes + tau * (kD * 2) + ((chunk ^ tau) & 15) * 16);
 }
 
 __device__ __forceinline__ void issue_v(const DecodeParams& p, int kvh, Pages pg, int v_lane_off, StepRegs& r)
@@ -156,24 +188,71 @@ struct WaveState {
     }
 };
 
-// One 32-token step on the registers in `r`.  After K has been consumed the K tiles of the wave's next
-// step (pages `next`) are requested into the same registers, and likewise V after the PV products, when
-// `more` says there is such a step.
+struct LaneIds {
+    int lane, wave, col, kg, tau, v_lane_off;
+    char* stage;             // this wave's K staging area in LDS
+    __device__ __forceinline__ LaneIds(char* stage_base)
+    {
+        lane = threadIdx.x & 63;
+        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        col = lane & 15;                                   // head column of S^T / O^T, dim group of V
+        kg = lane >> 4;                                    // k group
+        tau = 4 * (col & 3) + (col >> 2);                  // token whose K row this lane feeds to the MFMA
+        v_lane_off = lane * 16;
+        stage = stage_base + wave * kStageBytes;
+    }
+};
+
+// One 32-token step: K from the wave's LDS staging area, V from the registers in `r`.  When `more`
+// says the wave has a further step (pages `next` of kv head `next_kvh`: the same item's, or the first
+// step of the workgroup's next item), its K tiles are requested into the staging area as soon as this
+// step's K operands have been read out, and its V tiles into `r` after the PV products.
+//
+// Vector-memory operations retire in order, and every request for a step is "8 K loads, then 8 V
+// loads": once at most 8 operations are outstanding the K tiles have landed, whatever was issued
+// after them.
 __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
-                                            const u32x4 (&qb)[4], int s, bool ok_a, bool ok_b, bool more,
-                                            Pages next, int kg, int k_lane_off, int v_lane_off, float scale2)
+                                            const u32x4 (&qb)[4], const LaneIds& id, int s, bool ok_a, bool ok_b,
+                                            bool more, Pages next, int next_kvh, float scale2)
 {
+    const int kg = id.kg;
     // ---- S^T = K . Q^T for both pages ----------------------------------------------------------
+    OMNI_WAIT_VMCNT(8);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 ka[4], kb_[4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+        ka[kb] = read_k(id.stage, 0, kb, id.tau, kg);
+        kb_[kb] = read_k(id.stage, 1, kb, id.tau, kg);
+    }
+#ifdef OMNI_EXP_NOCOMPUTE
+    {   // experiment: same loads, trivial consumption
+        u32x4 x = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x ^= ka[i] ^ kb_[i];
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue_k(p, next_kvh, next, id.lane, id.stage);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x ^= r.va[i] ^ r.vb[i];
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue_v(p, next_kvh, next, id.v_lane_off, r);
+        __builtin_amdgcn_sched_barrier(0);
+        st.acc[0][0] += __uint_as_float((x.x ^ x.y ^ x.z ^ x.w) & 0x3f800000u) * (ok_a && ok_b ? 1.f : 2.f);
+        st.m_run = 0.f; st.l_run = 1.f;
+        return;
+    }
+#endif
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.ka[kb]),
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kb]),
                                                      __builtin_bit_cast(bf16x8, qb[kb]), sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.kb[kb]),
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb_[kb]),
                                                      __builtin_bit_cast(bf16x8, qb[kb]), sb, 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more) issue_k(p, it.kvh, next, k_lane_off, r);
+    if (more) issue_k(p, next_kvh, next, id.lane, id.stage);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- logits to the log2 domain, masking on boundary steps -----------------------------------
@@ -245,31 +324,56 @@ __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& i
         st.acc[2 * jj + 1] = a1;
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more) issue_v(p, it.kvh, next, v_lane_off, r);
+    if (more) issue_v(p, next_kvh, next, id.v_lane_off, r);
     __builtin_amdgcn_sched_barrier(0);
 }
 
 // All steps of an item that belong to this wave.  On entry the registers of the wave's first step are
 // already requested (if it has one).
+// What a wave streams after its last step of the current item: the first step of the workgroup's next
+// item (persistent form), or nothing.
+struct Tail {
+    bool valid;
+    int kvh;
+    Pages pages;
+};
+
+// All steps of an item that belong to this wave.  On entry the loads of the wave's first step are
+// already requested (if it has one).  In its last step the wave requests `tail` instead of a further
+// step of this item, and thread 0 draws the workgroup's next ticket (if `ticket_counter` is given and
+// wave 0 has a step at all; `drew` tells).
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
-                                         const u32x4 (&qb)[4], int wave, int kg, int k_lane_off, int v_lane_off,
-                                         float scale2, Pages cur)
+                                         const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur,
+                                         const Tail& tail, unsigned* ticket_counter, unsigned& ticket, bool& drew)
 {
-    int s = wave;
+    int s = id.wave;
     Pages nxt = {-1, -1};
     if (s + kWaves < it.n_steps) nxt = step_pages(p, it, s + kWaves);
+    // everything older than the first step's 8 K + 8 V requests (the item's Q above all) has landed
+    OMNI_WAIT_VMCNT(16);
     while (s < it.n_steps) {
-        const bool more = s + kWaves < it.n_steps;
+        const bool last = s + kWaves >= it.n_steps;
         Pages nn = {-1, -1};
         if (s + 2 * kWaves < it.n_steps) nn = step_pages(p, it, s + 2 * kWaves);   // table reads run a step ahead
-        attend_step(p, it, st, r, qb, s, cur.a >= 0, cur.b >= 0, more, nxt, kg, k_lane_off, v_lane_off, scale2);
+        if (last && ticket_counter) {
+            if (threadIdx.x == 0) ticket = atomicAdd(ticket_counter, 1u);
+            drew = true;
+        }
+        attend_step(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, !last || tail.valid, last ? tail.pages : nxt,
+                    last ? tail.kvh : it.kvh, scale2);
         cur = nxt;
         nxt = nn;
         s += kWaves;
     }
 }
 
-// LDS layout of the cross-wave combine: [kWaves][G][kD] accumulators, then [kWaves][16] m and l.
+// Dynamic LDS of a workgroup: the cross-wave combine area ([kWaves][G][kD] accumulators, then
+// [kWaves][16] m and l), then the waves' K staging areas.
+__host__ __device__ __forceinline__ size_t combine_bytes(int group)
+{
+    return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float);
+}
+
 __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds, int G, int wave, int col, int kg)
 {
     float l = st.l_run;
@@ -344,27 +448,13 @@ __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int 
     }
 }
 
-struct LaneIds {
-    int lane, wave, col, kg, k_lane_off, v_lane_off;
-    __device__ __forceinline__ LaneIds()
-    {
-        lane = threadIdx.x & 63;
-        wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        col = lane & 15;                                   // head column of S^T / O^T, dim group of V
-        kg = lane >> 4;                                    // k group
-        const int tau = 4 * (col & 3) + (col >> 2);        // token row this lane loads of K
-        k_lane_off = tau * (kD * 2) + kg * 16;
-        v_lane_off = lane * 16;
-    }
-};
-
 // ---------------------------------------------------------------------------------------------------
 // grid form
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodeParams p, const int* __restrict__ block_table)
 {
-    extern __shared__ float lds[];
-    const LaneIds id;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const LaneIds id(reinterpret_cast<char*>(lds) + combine_bytes(p.group));
     Item it;
     const int item = blockIdx.x;
     it.kvh = item % p.hkv;
@@ -387,10 +477,12 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodePar
     Pages cur = {-1, -1};
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
-        issue_k(p, it.kvh, cur, id.k_lane_off, r);
+        issue_k(p, it.kvh, cur, id.lane, id.stage);
         issue_v(p, it.kvh, cur, id.v_lane_off, r);
     }
-    run_item(p, it, st, r, qb, id.wave, id.kg, id.k_lane_off, id.v_lane_off, scale2, cur);
+    unsigned unused_ticket = 0;
+    bool unused_drew = false;
+    run_item(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, nullptr, unused_ticket, unused_drew);
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
     combine_and_store(p, it, lds, p.group);
@@ -410,25 +502,29 @@ __device__ __forceinline__ int sort_bin(int tokens, float bins_per_page)
     return (kSortBins - 1) - b;                            // bin 0 holds the longest ranges
 }
 
-// Wave-aggregated counter: every active lane adds one to counters[key]; lanes with equal keys are served
-// by a single LDS atomic.  Returns the lane's own slot (old value + rank among the lanes sharing its key).
-// Must be called by all lanes of the wave together.
-__device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, bool active)
+// Every active lane takes one slot of counters[key].  The two keys that whole waves tend to share (`hot_a`:
+// full chunks, `hot_b`: empty ones) are served by one LDS atomic per wave; the other keys, which differ
+// from lane to lane, by one atomic per lane.  Must be called by all lanes of the wave together.
+__device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, bool active, int hot_a, int hot_b)
 {
     const int lane = threadIdx.x & 63;
+    const unsigned long long below = (1ull << lane) - 1ull;
     unsigned slot = 0;
-    unsigned long long todo = __ballot(active);
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int k = __shfl(key, leader);
-        const bool mine = active && key == k;
+    bool served = !active;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int hot = h ? hot_b : hot_a;
+        const bool mine = active && key == hot;
         const unsigned long long grp = __ballot(mine);
-        unsigned base = 0;
-        if (lane == leader) base = atomicAdd(&counters[k], (unsigned)__popcll(grp));
-        base = __shfl(base, leader);
-        if (mine) slot = base + (unsigned)__popcll(grp & ((1ull << lane) - 1ull));
-        todo &= ~grp;
+        if (grp) {
+            const int leader = __builtin_ctzll(grp);
+            unsigned base = 0;
+            if (lane == leader) base = atomicAdd(&counters[hot], (unsigned)__popcll(grp));
+            base = __builtin_amdgcn_readlane(base, leader);
+            if (mine) { slot = base + (unsigned)__popcll(grp & below); served = true; }
+        }
     }
+    if (!served) slot = atomicAdd(&counters[key], 1u);
     return slot;
 }
 
@@ -436,25 +532,41 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 // `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
 // of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here).  Depends only on the ranges and the chunking, so a
 // list can serve every call that shares them (all layers of one decoding iteration).
+constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
+
 __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsigned* __restrict__ header,
                                                            WorkEntry* __restrict__ entries)
 {
     __shared__ unsigned hist[kSortBins + 1];               // last counter: empty entries
+    __shared__ int sh_b[kListCachedSeqs], sh_e[kListCachedSeqs];
     const int total = p.batch * p.max_chunks;
     const int max_pages = p.chunk_tokens / kBlockSize > 0 ? p.chunk_tokens / kBlockSize : 1;
     const float bins_per_page = (float)(kSortBins - 1) / (float)max_pages;
+    const bool cached = p.batch <= kListCachedSeqs;        // one trip to memory for the ranges, then LDS
     for (int i = threadIdx.x; i < kSortBins + 1; i += blockDim.x) hist[i] = 0;
+    if (cached) {
+        for (int i = threadIdx.x; i < p.batch; i += blockDim.x) {
+            int b, en;
+            seq_range(p, i, b, en);
+            sh_b[i] = b;
+            sh_e[i] = en;
+        }
+    }
     __syncthreads();
+    auto entry_range = [&](int e, int& seq, int& chunk, int& cb, int& ce) {
+        seq = e / p.max_chunks;
+        chunk = e - seq * p.max_chunks;
+        int b, en;
+        if (cached) { b = sh_b[seq]; en = sh_e[seq]; }
+        else seq_range(p, seq, b, en);
+        chunk_range(p, b, en, chunk, cb, ce);
+    };
     for (int base = 0; base < total; base += blockDim.x) {
         const int e = base + threadIdx.x;
-        int cb = 0, ce = 0;
-        if (e < total) {
-            int b, en;
-            seq_range(p, e / p.max_chunks, b, en);
-            chunk_range(p, b, en, e % p.max_chunks, cb, ce);
-        }
+        int seq, chunk, cb = 0, ce = 0;
+        if (e < total) entry_range(e, seq, chunk, cb, ce);
         const bool live = ce > cb;
-        wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total);
+        wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total, 0, kSortBins);
     }
     __syncthreads();
     if (threadIdx.x < kWave) {                             // exclusive scan by one wave: bin -> first output slot
@@ -482,16 +594,11 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
     __syncthreads();
     for (int base = 0; base < total; base += blockDim.x) {
         const int e = base + threadIdx.x;
-        int cb = 0, ce = 0, seq = 0, chunk = 0;
-        if (e < total) {
-            int b, en;
-            seq = e / p.max_chunks;
-            chunk = e % p.max_chunks;
-            seq_range(p, seq, b, en);
-            chunk_range(p, b, en, chunk, cb, ce);
-        }
+        int seq = 0, chunk = 0, cb = 0, ce = 0;
+        if (e < total) entry_range(e, seq, chunk, cb, ce);
         const bool live = ce > cb;
-        const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total);
+        const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total, 0,
+                                             kSortBins);
         if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, chunk, cb, ce};
     }
 }
@@ -508,7 +615,7 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
 }
 
 #ifndef OMNI_P_OCC
-#define OMNI_P_OCC 2
+#define OMNI_P_OCC 3
 #endif
 #ifndef OMNI_P_HOIST
 #define OMNI_P_HOIST 1
@@ -520,9 +627,9 @@ __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ unsigned sh_ticket[3];
-    const LaneIds id;
+    const LaneIds id(reinterpret_cast<char*>(lds) + combine_bytes(p.group));
     const unsigned n_tickets = counts[0] * (unsigned)p.hkv;
     const float scale2 = p.sm_scale * kLog2e;
 
@@ -554,51 +661,41 @@ __device__ __forceinline__ void persistent_body(
     Pages cur = {-1, -1};
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
-        issue_k(p, it.kvh, cur, id.k_lane_off, r);
+        issue_k(p, it.kvh, cur, id.lane, id.stage);
         issue_v(p, it.kvh, cur, id.v_lane_off, r);
     }
     for (int k = 0;; ++k) {
-        unsigned t2 = 0;                                   // ticket of the item after next, drawn early
-        if (threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
-
         // the next item's description and first pages are fetched while this item streams
         const unsigned tn = __builtin_amdgcn_readfirstlane(sh_ticket[(k + 1) % 3]);
         const bool has_next = tn < n_tickets;
         Item nx = it;
-        Pages nx_first = {-1, -1};
-#if OMNI_P_HOIST
+        Tail tail = {false, 0, Pages{-1, -1}};
         if (has_next) {
             nx = ticket_item(p, entries, block_table, tn);
-            if (id.wave < nx.n_steps) nx_first = step_pages(p, nx, id.wave);
+            if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
         }
-#endif
 
-        run_item(p, it, st, r, qb, id.wave, id.kg, id.k_lane_off, id.v_lane_off, scale2, cur);
+        // The ticket of the item after next is drawn by thread 0 in its wave's last step of this item
+        // (late, so that tickets stay with whoever gets to them first), or right after if wave 0 has
+        // no step here.  Waves stream the first step of the next item right behind their last step.
+        unsigned t2 = 0;
+        bool drew = false;
+        const bool streamed = id.wave < it.n_steps;
+        run_item(p, it, st, r, qb, id, scale2, cur, tail, ticket_counter, t2, drew);
+        if (!drew && threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
 
-#if !OMNI_P_HOIST
-        if (has_next) {
-            nx = ticket_item(p, entries, block_table, tn);
-            if (id.wave < nx.n_steps) nx_first = step_pages(p, nx, id.wave);
-        }
-#endif
-
-        // accumulators go to LDS, then the next item's Q and first step are requested, and only then the
-        // workgroup meets for the combine: the loads fly during both barriers
-#if OMNI_P_STAGE_FIRST
+        // accumulators go to LDS, the next item's Q is requested (and its first step by the waves that
+        // had no step in this item), and only then the workgroup meets for the combine
         stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
-#endif
-        if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
         if (has_next) {
             load_q(p, nx, id.col, id.kg, qb);
-            cur = nx_first;
-            if (id.wave < nx.n_steps) {
-                issue_k(p, nx.kvh, cur, id.k_lane_off, r);
+            cur = tail.pages;
+            if (tail.valid && !streamed) {
+                issue_k(p, nx.kvh, cur, id.lane, id.stage);
                 issue_v(p, nx.kvh, cur, id.v_lane_off, r);
             }
         }
-#if !OMNI_P_STAGE_FIRST
-        stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
-#endif
+        if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
         __syncthreads();
         combine_and_store(p, it, lds, p.group);
         if (!has_next) break;
@@ -624,7 +721,7 @@ __global__ __launch_bounds__(kThreads, OMNI_P_OCC) void decode_mfma_persistent_k
     }
 }
 
-size_t lds_bytes(int group) { return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float); }
+size_t lds_bytes(int group) { return combine_bytes(group) + (size_t)kWaves * kStageBytes; }
 
 }  // namespace
 
@@ -649,9 +746,16 @@ hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_
 
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s)
 {
+    const size_t lds = lds_bytes(p.group);
+    if (lds > 64 * 1024) {                                 // G = 16 only: ask for the larger LDS window
+        hipError_t ea = hipFuncSetAttribute(workspace ? (const void*)decode_mfma_persistent_kernel
+                                                      : (const void*)decode_mfma_grid_kernel,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (ea != hipSuccess) return ea;
+    }
     if (!workspace) {
         const unsigned grid = (unsigned)((long long)p.batch * p.max_chunks * p.hkv);
-        hipLaunchKernelGGL(decode_mfma_grid_kernel, dim3(grid), dim3(kThreads), lds_bytes(p.group), s, p, p.block_table);
+        hipLaunchKernelGGL(decode_mfma_grid_kernel, dim3(grid), dim3(kThreads), lds, s, p, p.block_table);
         return hipGetLastError();
     }
     int dev = 0, cus = 0;
@@ -668,7 +772,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     // more workgroups than can be resident are harmless: late ones find the tickets gone
     long long want = (long long)cus * 4, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
-    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds_bytes(p.group), s, p,
+    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds, s, p,
                        p.block_table, header, header + 1, entries);
     return hipGetLastError();
 }
