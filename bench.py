@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per decode-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor the same counters show for the plain copy kernel; None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg3-gqa-b256": 1996.3e6}      # profiles/decode_mfma_persistent_cfg3_pmc.md
 
 
 def algorithmic_bytes(w) -> int:
@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--pools", type=int, default=2, help="physical KV pool copies rotated between steps")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector, 2 matrix-core")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the plain 1 GiB copy kernel a few times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
@@ -81,16 +83,32 @@ def main() -> int:
     kv_bytes = w.kv_bytes()
     alg_bytes = algorithmic_bytes(w)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.omni_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # One step = work list + decode attention (the dominant kernel, bracketed by events on its own
+    # stream) + merge.  The list is rebuilt every step, as a caller without plan reuse would.
+    def step(i, e0=None, e1=None):
+        dw.plan()
+        if e0 is not None:
+            e0.record()
+        dw.run_attention(kernel=args.kernel, pool=i % args.pools, planned=True)
+        if e1 is not None:
+            e1.record()
+        dw.run_merge()
+
     for i in range(args.warmup):
-        dw.run(kernel=args.kernel, pool=i % args.pools)
+        step(i)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ev[i][0].record()
-        dw.run_attention(kernel=args.kernel, pool=i % args.pools)
-        ev[i][1].record()
-        dw.run_merge()
+        step(i, *ev[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     step_ms = (t1 - t0) * 1e3 / args.steps
@@ -116,7 +134,9 @@ def main() -> int:
         "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "kernel": "decode attention", "algorithmic_bytes_per_launch": alg_bytes // len(w.calls)},
+                     "kernel": "decode_mfma_persistent_kernel" if dw.calls[0]["workspace"] is not None and
+                     w.dtype == "bf16" and w.head_dim == 128 and args.kernel != 1 else "decode attention",
+                     "algorithmic_bytes_per_launch": alg_bytes // len(w.calls)},
     }
 
     if not args.no_cpu_baseline:
@@ -125,16 +145,19 @@ def main() -> int:
         per_seq = w.ctx_len.astype(np.int64) * 2 * w.num_kv_heads * w.head_dim * w.elem_bytes
         n_seq = int(min(w.batch, max(1, np.searchsorted(np.cumsum(per_seq), 2.2e9) + 1)))
         seqs = np.arange(n_seq)
+        reps = 0
         c0 = time.perf_counter()
-        oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, None, w.ctx_len, w.sm_scale, w.dtype,
-                          seqs=seqs, n_threads=cores)
+        while reps < 20 and (reps == 0 or time.perf_counter() - c0 < 1.5):      # ~20-30 core-seconds of work
+            oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, None, w.ctx_len, w.sm_scale, w.dtype,
+                              seqs=seqs, n_threads=cores)
+            reps += 1
         c1 = time.perf_counter()
-        sample_bytes = int(per_seq[:n_seq].sum())
+        sample_bytes = int(per_seq[:n_seq].sum()) * reps
         out["cpu_baseline"] = {"value": sample_bytes / (c1 - c0) / 1e9, "unit": "GB/s", "cores": cores,
                                "kind": "oracle",
                                "sample": "fp64 oracle, attention of the first %d of %d sequences (all heads, "
-                                         "full contexts, %.2f GB of KV), %.2f s wall" %
-                                         (n_seq, w.batch, sample_bytes / 1e9, c1 - c0)}
+                                         "full contexts), %d passes, %.2f GB of KV in all, %.2f s wall" %
+                                         (n_seq, w.batch, reps, sample_bytes / 1e9, c1 - c0)}
     print(json.dumps(out))
     return 0
 

@@ -29,11 +29,21 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     if (row >= (long long)p.batch * p.hq) return;
     const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
 
+    // Rows are visited four at a time so that four independent loads are in flight per lane: the kernel
+    // is a handful of dependent memory round trips, not a bandwidth problem.
+    constexpr int kBatch = 4;
     float m = -INFINITY;
     for (int s = 0; s < p.n_srcs; ++s) {
         int r0, r1;
         src_rows(p.src[s], seq, r0, r1);
-        for (int r = r0; r < r1; ++r) m = fmaxf(m, p.src[s].lse[(long long)r * p.hq + head]);
+        const float* lse = p.src[s].lse + head;
+        for (int r = r0; r < r1; r += kBatch) {
+            float l[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) l[u] = (r + u < r1) ? lse[(long long)(r + u) * p.hq] : -INFINITY;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) m = fmaxf(m, l[u]);
+        }
     }
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.f;
@@ -41,14 +51,27 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
         for (int s = 0; s < p.n_srcs; ++s) {
             int r0, r1;
             src_rows(p.src[s], seq, r0, r1);
-            for (int r = r0; r < r1; ++r) {
-                float lse = p.src[s].lse[(long long)r * p.hq + head];
-                if (lse == -INFINITY) continue;
-                float w = expf(lse - m);
-                float4 o = *reinterpret_cast<const float4*>(p.src[s].o + ((long long)r * p.hq + head) * D + quad * 4);
-                wsum += w;
-                acc.x = fmaf(w, o.x, acc.x); acc.y = fmaf(w, o.y, acc.y);
-                acc.z = fmaf(w, o.z, acc.z); acc.w = fmaf(w, o.w, acc.w);
+            const float* lse = p.src[s].lse + head;
+            const float* orow = p.src[s].o + (long long)head * D + quad * 4;
+            for (int r = r0; r < r1; r += kBatch) {
+                float w[kBatch];
+                float4 o[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float l = (r + u < r1) ? lse[(long long)(r + u) * p.hq] : -INFINITY;
+                    w[u] = (l == -INFINITY) ? 0.f : expf(l - m);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {       // a row without weight is not read at all
+                    o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (w[u] != 0.f) o[u] = *reinterpret_cast<const float4*>(orow + (long long)(r + u) * p.hq * D);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    wsum += w[u];
+                    acc.x = fmaf(w[u], o[u].x, acc.x); acc.y = fmaf(w[u], o[u].y, acc.y);
+                    acc.z = fmaf(w[u], o[u].z, acc.z); acc.w = fmaf(w[u], o[u].w, acc.w);
+                }
             }
         }
         float inv = 1.f / wsum;
