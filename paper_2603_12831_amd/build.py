@@ -21,6 +21,8 @@ SOURCES = ["api.hip", "decode_vector.hip", "decode_mfma.hip", "merge.hip", "debu
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep single-lane ticket atomics as issued (the wave-aggregation rewrite waits on them at once)
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

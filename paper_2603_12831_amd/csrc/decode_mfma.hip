@@ -328,8 +328,6 @@ __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& i
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// All steps of an item that belong to this wave.  On entry the registers of the wave's first step are
-// already requested (if it has one).
 // What a wave streams after its last step of the current item: the first step of the workgroup's next
 // item (persistent form), or nothing.
 struct Tail {
@@ -339,36 +337,72 @@ struct Tail {
 };
 
 // All steps of an item that belong to this wave.  On entry the loads of the wave's first step are
-// already requested (if it has one).  In its last step the wave requests `tail` instead of a further
-// step of this item, and thread 0 draws the workgroup's next ticket (if `ticket_counter` is given and
-// wave 0 has a step at all; `drew` tells).
+// already requested (if it has one).  The wave's last step is peeled off: `before_last` runs right before
+// it and `after_last` right after, and during it the wave requests `tail` instead of a further step of
+// this item.
+template <class Before, class After>
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                          const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur,
-                                         const Tail& tail, unsigned* ticket_counter, unsigned& ticket, bool& drew)
+                                         const Tail& tail, Before&& before_last, After&& after_last)
 {
     int s = id.wave;
     Pages nxt = {-1, -1};
     if (s + kWaves < it.n_steps) nxt = step_pages(p, it, s + kWaves);
-    // everything older than the first step's 8 K + 8 V requests (the item's Q above all) has landed
+    // everything older than the first step's 8 K + 8 V requests has landed
     OMNI_WAIT_VMCNT(16);
-    while (s < it.n_steps) {
-        const bool last = s + kWaves >= it.n_steps;
+    while (s + kWaves < it.n_steps) {
         Pages nn = {-1, -1};
         if (s + 2 * kWaves < it.n_steps) nn = step_pages(p, it, s + 2 * kWaves);   // table reads run a step ahead
-        if (last && ticket_counter) {
-            if (threadIdx.x == 0) ticket = atomicAdd(ticket_counter, 1u);
-            drew = true;
-        }
-        attend_step(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, !last || tail.valid, last ? tail.pages : nxt,
-                    last ? tail.kvh : it.kvh, scale2);
+        attend_step(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, true, nxt, it.kvh, scale2);
         cur = nxt;
         nxt = nn;
         s += kWaves;
     }
+    if (s < it.n_steps) {
+        before_last();
+        attend_step(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.valid, tail.pages, tail.kvh, scale2);
+        after_last();
+    }
+}
+
+// Workgroup barrier that orders LDS traffic only: vector-memory loads already in flight (the prefetch of
+// the next step or item) stay in flight across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    // LDS writes of this wave done (lgkmcnt), then the barrier; the memory clobber keeps the compiler from
+    // moving LDS accesses across.  A fence would also wait for the direct-to-LDS loads in flight, which
+    // only ever target the issuing wave's own staging area.
+#ifndef OMNI_EXP_NOBARRIER
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#else
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+}
+
+// Q rows of an item's G heads into an LDS buffer ([g][256 bytes]) by one wave's direct-to-LDS loads:
+// lane l moves 16 bytes of row 4i + l/16 in round i; lanes of rows >= G stay idle.
+__device__ __forceinline__ void issue_q(const DecodeParams& p, const Item& it, int lane, char* qbuf)
+{
+    const long long row0 = (long long)it.seq * p.hq + (long long)it.kvh * p.group;
+    const char* src = static_cast<const char*>(p.q) + row0 * (kD * 2) + lane * 16;
+    for (int i = 0; 4 * i < p.group; ++i) {
+        if (4 * i + (lane >> 4) < p.group)
+            __builtin_amdgcn_global_load_lds((global_void*)(src + i * 1024), (lds_void*)(qbuf + i * 1024), 16, 0, 0);
+    }
+}
+
+// Q^T operands from the LDS copy: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are
+// zero columns
+__device__ __forceinline__ void read_q(const char* qbuf, int group, int col, int kg, u32x4 (&qb)[4])
+{
+    const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+        qb[kb] = (col < group) ? *reinterpret_cast<const u32x4*>(qbuf + col * (kD * 2) + (kb * 4 + kg) * 16) : z;
 }
 
 // Dynamic LDS of a workgroup: the cross-wave combine area ([kWaves][G][kD] accumulators, then
-// [kWaves][16] m and l), then the waves' K staging areas.
+// [kWaves][16] m and l), the waves' K staging areas and, in the persistent form, two Q buffers.
 __host__ __device__ __forceinline__ size_t combine_bytes(int group)
 {
     return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float);
@@ -418,7 +452,11 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             }
             o = oo / ll;
             lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
+#ifndef OMNI_EXP_NOSTORE
             if (p.part_o) p.part_o[(prow0 + g) * kD + d] = o;
+#else
+            if (p.part_o && o == 123.456f) p.part_o[(prow0 + g) * kD + d] = o;
+#endif
         }
         if (p.part_lse && d == 0) p.part_lse[prow0 + g] = lse;
         if (final_row) {
@@ -480,9 +518,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodePar
         issue_k(p, it.kvh, cur, id.lane, id.stage);
         issue_v(p, it.kvh, cur, id.v_lane_off, r);
     }
-    unsigned unused_ticket = 0;
-    bool unused_drew = false;
-    run_item(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, nullptr, unused_ticket, unused_drew);
+    run_item(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, [] {}, [] {});
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
     combine_and_store(p, it, lds, p.group);
@@ -614,22 +650,16 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     return it;
 }
 
-#ifndef OMNI_P_OCC
-#define OMNI_P_OCC 3
-#endif
-#ifndef OMNI_P_HOIST
-#define OMNI_P_HOIST 1
-#endif
-#ifndef OMNI_P_STAGE_FIRST
-#define OMNI_P_STAGE_FIRST 1
-#endif
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ unsigned sh_ticket[3];
-    const LaneIds id(reinterpret_cast<char*>(lds) + combine_bytes(p.group));
+    char* const stage_base = reinterpret_cast<char*>(lds) + combine_bytes(p.group);
+    char* const q_base = stage_base + kWaves * kStageBytes;          // two buffers of G rows, by item parity
+    const int q_bytes = p.group * kD * 2;
+    const LaneIds id(stage_base);
     const unsigned n_tickets = counts[0] * (unsigned)p.hkv;
     const float scale2 = p.sm_scale * kLog2e;
 
@@ -652,11 +682,9 @@ __device__ __forceinline__ void persistent_body(
     unsigned tk = __builtin_amdgcn_readfirstlane(sh_ticket[0]);
     if (tk >= n_tickets) return;
 
+    // first item: wave 0 brings Q into LDS, every wave requests its first step, then all read Q
     Item it = ticket_item(p, entries, block_table, tk);
-    u32x4 qb[4];
-    load_q(p, it, id.col, id.kg, qb);
-    WaveState st;
-    st.reset();
+    if (id.wave == 0) issue_q(p, it, id.lane, q_base);
     StepRegs r;
     Pages cur = {-1, -1};
     if (id.wave < it.n_steps) {
@@ -664,6 +692,13 @@ __device__ __forceinline__ void persistent_body(
         issue_k(p, it.kvh, cur, id.lane, id.stage);
         issue_v(p, it.kvh, cur, id.v_lane_off, r);
     }
+    OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
+    lds_barrier();
+    u32x4 qb[4];
+    read_q(q_base, p.group, id.col, id.kg, qb);
+    WaveState st;
+    st.reset();
+
     for (int k = 0;; ++k) {
         // the next item's description and first pages are fetched while this item streams
         const unsigned tn = __builtin_amdgcn_readfirstlane(sh_ticket[(k + 1) % 3]);
@@ -674,32 +709,38 @@ __device__ __forceinline__ void persistent_body(
             nx = ticket_item(p, entries, block_table, tn);
             if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
         }
+        char* const q_next = q_base + ((k + 1) & 1) * q_bytes;
 
-        // The ticket of the item after next is drawn by thread 0 in its wave's last step of this item
-        // (late, so that tickets stay with whoever gets to them first), or right after if wave 0 has
-        // no step here.  Waves stream the first step of the next item right behind their last step.
+        // Right before its last step of this item wave 0 requests the next item's Q (into the other Q
+        // buffer) and thread 0 draws the ticket of the item after next (late, so that tickets go to
+        // whoever gets there first); in the last step every wave streams the first step of the next item
+        // instead of a further step of this one.  Wave 0 has a step in every item.
         unsigned t2 = 0;
-        bool drew = false;
         const bool streamed = id.wave < it.n_steps;
-        run_item(p, it, st, r, qb, id, scale2, cur, tail, ticket_counter, t2, drew);
-        if (!drew && threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
+        run_item(p, it, st, r, qb, id, scale2, cur, tail,
+                 [&] {
+                     if (has_next && id.wave == 0) issue_q(p, nx, id.lane, q_next);
+                     if (threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
+                 },
+                 [&] {
+                     if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
+                 });
 
-        // accumulators go to LDS, the next item's Q is requested (and its first step by the waves that
-        // had no step in this item), and only then the workgroup meets for the combine
+        // accumulators go to LDS; waves that had no step in this item request their first step of the next
+        // one now; wave 0 makes sure the next Q has landed (it is older than the 16 K/V requests behind
+        // it); then the workgroup meets for the combine with all those loads still in flight
         stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
-        if (has_next) {
-            load_q(p, nx, id.col, id.kg, qb);
-            cur = tail.pages;
-            if (tail.valid && !streamed) {
-                issue_k(p, nx.kvh, cur, id.lane, id.stage);
-                issue_v(p, nx.kvh, cur, id.v_lane_off, r);
-            }
+        cur = tail.pages;
+        if (tail.valid && !streamed) {
+            issue_k(p, nx.kvh, cur, id.lane, id.stage);
+            issue_v(p, nx.kvh, cur, id.v_lane_off, r);
         }
-        if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
-        __syncthreads();
+        if (id.wave == 0) OMNI_WAIT_VMCNT(16);
+        lds_barrier();
         combine_and_store(p, it, lds, p.group);
         if (!has_next) break;
-        __syncthreads();                                   // LDS is rewritten by the next item's staging
+        lds_barrier();                                     // LDS is rewritten by the next item's staging
+        read_q(q_next, p.group, id.col, id.kg, qb);
         st.reset();
         it = nx;
     }
@@ -707,7 +748,7 @@ __device__ __forceinline__ void persistent_body(
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts both back to zero, so the same list can serve the next call.
-__global__ __launch_bounds__(kThreads, OMNI_P_OCC) void decode_mfma_persistent_kernel(
+__global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
 {
@@ -721,7 +762,10 @@ __global__ __launch_bounds__(kThreads, OMNI_P_OCC) void decode_mfma_persistent_k
     }
 }
 
-size_t lds_bytes(int group) { return combine_bytes(group) + (size_t)kWaves * kStageBytes; }
+size_t lds_bytes(int group, bool persistent)
+{
+    return combine_bytes(group) + (size_t)kWaves * kStageBytes + (persistent ? 2 * (size_t)group * kD * 2 : 0);
+}
 
 }  // namespace
 
@@ -746,7 +790,7 @@ hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_
 
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s)
 {
-    const size_t lds = lds_bytes(p.group);
+    const size_t lds = lds_bytes(p.group, workspace != nullptr);
     if (lds > 64 * 1024) {                                 // G = 16 only: ask for the larger LDS window
         hipError_t ea = hipFuncSetAttribute(workspace ? (const void*)decode_mfma_persistent_kernel
                                                       : (const void*)decode_mfma_grid_kernel,
