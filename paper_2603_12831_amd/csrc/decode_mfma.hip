@@ -225,24 +225,6 @@ __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& i
         ka[kb] = read_k(id.stage, 0, kb, id.tau, kg);
         kb_[kb] = read_k(id.stage, 1, kb, id.tau, kg);
     }
-#ifdef OMNI_EXP_NOCOMPUTE
-    {   // experiment: same loads, trivial consumption
-        u32x4 x = {0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x ^= ka[i] ^ kb_[i];
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) issue_k(p, next_kvh, next, id.lane, id.stage);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) x ^= r.va[i] ^ r.vb[i];
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) issue_v(p, next_kvh, next, id.v_lane_off, r);
-        __builtin_amdgcn_sched_barrier(0);
-        st.acc[0][0] += __uint_as_float((x.x ^ x.y ^ x.z ^ x.w) & 0x3f800000u) * (ok_a && ok_b ? 1.f : 2.f);
-        st.m_run = 0.f; st.l_run = 1.f;
-        return;
-    }
-#endif
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) {
@@ -372,11 +354,7 @@ __device__ __forceinline__ void lds_barrier()
     // LDS writes of this wave done (lgkmcnt), then the barrier; the memory clobber keeps the compiler from
     // moving LDS accesses across.  A fence would also wait for the direct-to-LDS loads in flight, which
     // only ever target the issuing wave's own staging area.
-#ifndef OMNI_EXP_NOBARRIER
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#else
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
 }
 
 // Q rows of an item's G heads into an LDS buffer ([g][256 bytes]) by one wave's direct-to-LDS loads:
@@ -452,11 +430,7 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             }
             o = oo / ll;
             lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
-#ifndef OMNI_EXP_NOSTORE
             if (p.part_o) p.part_o[(prow0 + g) * kD + d] = o;
-#else
-            if (p.part_o && o == 123.456f) p.part_o[(prow0 + g) * kD + d] = o;
-#endif
         }
         if (p.part_lse && d == 0) p.part_lse[prow0 + g] = lse;
         if (final_row) {

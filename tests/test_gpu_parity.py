@@ -309,6 +309,45 @@ def test_deterministic_and_placement_independent(kernel):
     assert np.array_equal(o1, o3) and np.array_equal(l1, l3)
 
 
+@pytest.mark.parametrize("kernel", KERNELS[1:])
+@pytest.mark.parametrize("shape", [(16, 1, 128), (8, 8, 128), (6, 3, 128), (24, 3, 128), (32, 2, 128)])
+def test_matrix_core_group_sizes(kernel, shape):
+    """GQA ratios 16, 1, 2, 8 and 16 (the last needs the large LDS window) with ragged chunked contexts."""
+    hq, hkv, d = shape
+    rng = np.random.default_rng(hq * 100 + hkv)
+    lengths = rng.integers(1, 900, size=9)
+    w = wl.make_generic(61, lengths, hq, hkv, d, dtype="bf16", chunk_tokens=160, pool_factor=1.3)
+    run_and_check(w, kernel)
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 0, 1
+    run_and_check(w, kernel)
+
+
+def test_work_list_with_many_sequences():
+    """More sequences than the list kernel keeps in LDS (2048), most of them short, some empty."""
+    rng = np.random.default_rng(62)
+    lengths = rng.integers(0, 40, size=2500)
+    lengths[::97] = 0
+    lengths[5] = 700
+    w = wl.make_generic(62, np.maximum(lengths, 1), 4, 1, 128, dtype="bf16", chunk_tokens=32)
+    w.calls[0].ctx_end = lengths.astype(np.int32)
+    run_and_check(w, BENCH_FORM)
+    run_and_check(w, (binding.OMNI_KERNEL_AUTO, False))
+
+
+def test_workspace_too_small_is_rejected():
+    w = wl.make_generic(63, [100, 50], 8, 2, 128, dtype="bf16", chunk_tokens=32)
+    dw = DeviceWorkload(w, out_dtype="f32")
+    c = dw.calls[0]
+    small = torch.empty(64, dtype=torch.uint8, device=dw.device)
+    st = binding.omni_paged_decode_attn(dw.q, dw.k_pools[0], dw.v_pools[0], dw.block_table, c["begin"], c["end"],
+                                        sm_scale=w.sm_scale, chunk_tokens=32, max_chunks=c["max_chunks"],
+                                        part_o=c["part_o"], part_lse=c["part_lse"], workspace=small, check=False)
+    assert st == binding.OMNI_ERR_SHAPE
+    # the vector kernel ignores a workspace
+    wf = wl.make_generic(63, [100, 50], 8, 2, 64, dtype="f32", chunk_tokens=32)
+    run_and_check(wf, (binding.OMNI_KERNEL_AUTO, True))
+
+
 def test_plan_once_serves_many_passes():
     """One work list (omni_decode_plan) reused by several attention passes over the same ranges,
     as the layers of one decoding iteration would: results equal the self-planning call bit for bit."""
