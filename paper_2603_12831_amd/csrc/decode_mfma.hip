@@ -157,6 +157,18 @@ __device__ __forceinline__ void issue_v(const DecodeParams& p, int kvh, Pages pg
     load_tile(p.v_pool, p.hkv, pg.b, kvh, v_lane_off, 1024, r.vb);
 }
 
+// Request a whole step: the 8 K loads strictly before the 8 V loads (the in-order counting of
+// attend_step relies on that order, so the scheduler must not swap them).
+__device__ __forceinline__ void issue_step(const DecodeParams& p, int kvh, Pages pg, int lane, char* stage,
+                                           int v_lane_off, StepRegs& r)
+{
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k(p, kvh, pg, lane, stage);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v(p, kvh, pg, v_lane_off, r);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // Q^T operands: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are zero columns
 __device__ __forceinline__ void load_q(const DecodeParams& p, const Item& it, int col, int kg, u32x4 (&qb)[4])
 {
@@ -489,8 +501,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodePar
     Pages cur = {-1, -1};
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
-        issue_k(p, it.kvh, cur, id.lane, id.stage);
-        issue_v(p, it.kvh, cur, id.v_lane_off, r);
+        issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
     run_item(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, [] {}, [] {});
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
@@ -663,8 +674,7 @@ __device__ __forceinline__ void persistent_body(
     Pages cur = {-1, -1};
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
-        issue_k(p, it.kvh, cur, id.lane, id.stage);
-        issue_v(p, it.kvh, cur, id.v_lane_off, r);
+        issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
@@ -706,8 +716,7 @@ __device__ __forceinline__ void persistent_body(
         stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
         cur = tail.pages;
         if (tail.valid && !streamed) {
-            issue_k(p, nx.kvh, cur, id.lane, id.stage);
-            issue_v(p, nx.kvh, cur, id.v_lane_off, r);
+            issue_step(p, nx.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
         }
         if (id.wave == 0) OMNI_WAIT_VMCNT(16);
         lds_barrier();
