@@ -551,7 +551,8 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 
 // Work list of a call: the non-empty (sequence, chunk) ranges, longest first, from the front of
 // `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
-// of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here).  Depends only on the ranges and the chunking, so a
+// of non-empty entries, word 2 number of empty ones, words 3 and 4 counts of departed / arrived workgroups
+// (zeroed here).  Depends only on the ranges and the chunking, so a
 // list can serve every call that shares them (all layers of one decoding iteration).
 constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
 
@@ -609,6 +610,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
             header[1] = incl;
             header[2] = hist[kSortBins];
             header[3] = 0;
+            header[4] = 0;
             hist[kSortBins] = 0;
         }
     }
@@ -658,10 +660,15 @@ __device__ __forceinline__ void persistent_body(
         }
     }
 
-    if (threadIdx.x == 0) {                                // the workgroup's first two tickets
-        const unsigned t = atomicAdd(ticket_counter, 2u);
-        sh_ticket[0] = t;
-        sh_ticket[1] = t + 1;
+    // The first two tickets of a workgroup are fixed by its arrival number a among the N launched
+    // (all resident) workgroups: a and 2N-1-a.  With the list longest-first that pairs the longest items
+    // with the shortest of the first 2N, which is what a longest-first greedy assignment would do; tickets
+    // from 2N on are drawn one at a time as workgroups get to them.
+    const unsigned first_dynamic = 2u * gridDim.x;
+    if (threadIdx.x == 0) {
+        const unsigned a = atomicAdd(ticket_counter + 4, 1u);
+        sh_ticket[0] = a;
+        sh_ticket[1] = first_dynamic - 1u - a;
     }
     __syncthreads();
     unsigned tk = __builtin_amdgcn_readfirstlane(sh_ticket[0]);
@@ -704,7 +711,7 @@ __device__ __forceinline__ void persistent_body(
         run_item(p, it, st, r, qb, id, scale2, cur, tail,
                  [&] {
                      if (has_next && id.wave == 0) issue_q(p, nx, id.lane, q_next);
-                     if (threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
+                     if (threadIdx.x == 0) t2 = first_dynamic + atomicAdd(ticket_counter, 1u);
                  },
                  [&] {
                      if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = t2;
@@ -729,8 +736,9 @@ __device__ __forceinline__ void persistent_body(
     }
 }
 
-// Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
-// list; the last workgroup to leave puts both back to zero, so the same list can serve the next call.
+// Header words 0 (ticket counter), 3 (workgroups that have left) and 4 (workgroups that have arrived) are
+// the only mutable state of a work list; the last workgroup to leave puts them back to zero, so the same
+// list can serve the next call.
 __global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
@@ -740,6 +748,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
             atomicExch(header + 3, 0u);
+            atomicExch(header + 4, 0u);
             atomicExch(header, 0u);
         }
     }
@@ -796,8 +805,13 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
         e = launch_decode_plan(p, workspace, s);
         if (e != hipSuccess) return e;
     }
-    // more workgroups than can be resident are harmless: late ones find the tickets gone
-    long long want = (long long)cus * 4, cap = (long long)p.batch * p.max_chunks * p.hkv;
+    // exactly as many workgroups as are resident at once: the first two tickets of each are fixed by its
+    // arrival number, so none may have to wait for another to leave
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kThreads, lds);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) return hipErrorLaunchOutOfResources;
+    long long want = (long long)cus * per_cu, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds, s, p,
                        p.block_table, header, header + 1, entries);
