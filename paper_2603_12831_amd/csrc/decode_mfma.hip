@@ -14,8 +14,10 @@
 // and eight consecutive k of group l/16; the result puts col l%16, rows
 // 4*(l/16)+i in register i.
 //
-//   * K is loaded straight into the A layout: lane l reads 16 bytes of token
-//     row tau(l%16) at dims kb*32 + (l/16)*8, tau(r) = 4*(r%4) + r/4.
+//   * K goes from memory straight into a per-wave LDS staging area (direct-to-LDS
+//     16-byte loads, whole 256-byte rows per 16 lanes, XOR-swizzled image) and is
+//     read from there in the A layout: lane l takes token row tau(l%16) at dims
+//     kb*32 + (l/16)*8, tau(r) = 4*(r%4) + r/4, conflict-free.
 //   * With that token order the S^T result registers of a lane (tokens
 //     4i + l/16, i = 0..3, of each page) are exactly the k-slots the lane must
 //     supply for P^T, so softmax weights never cross lanes.
@@ -39,11 +41,11 @@
 //   * grid form: one workgroup per (sequence, chunk, kv head) slot of the
 //     partial buffers, empty slots exit at once; needs no workspace.
 //   * persistent form (caller gave a workspace): a one-workgroup pass lists the
-//     non-empty (sequence, chunk) ranges longest-first and writes LSE = -inf for
-//     the empty ones; persistent workgroups then draw items from that list with
-//     an atomic ticket, and issue the first loads of their next item before the
-//     cross-wave combine of the current one, so the memory pipe never drains
-//     between items and the longest items cannot end up last.
+//     non-empty (sequence, chunk) ranges longest-first and the empty ones apart;
+//     one resident workgroup per slot of the chip then draws items from that list
+//     with atomic tickets, and in its last step of an item already requests the
+//     first step of its next item, so the memory pipe never drains between items
+//     and the longest items cannot end up last.
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -128,7 +130,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t byte_buffer(const void* base, 
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
-constexpr int kAuxK = 0;                               // cache policy of the K loads (see load_tile for V)                     // cache-policy bit "nt" of gfx94x/gfx950 memory loads
+constexpr int kAuxK = 0;                               // cache policy of the K loads: default (V: see load_tile)
 
 // K tiles of a step go from HBM straight into the wave's LDS staging area (no registers while in
 // flight).  A wave-wide 16-byte direct load puts lane s's data at base + 16 s, so for KiB i of a page
