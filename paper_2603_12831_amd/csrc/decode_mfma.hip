@@ -496,10 +496,12 @@ __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int 
 // ---------------------------------------------------------------------------------------------------
 // grid form
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodeParams p, const int* __restrict__ block_table)
+__global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodeParams p, const int* __restrict__ block_table)
 {
+    // the K staging areas and the combine area share the same LDS: the combine starts after a barrier
+    // behind every wave's last K read, and nothing is in flight by then in this form
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    const LaneIds id(reinterpret_cast<char*>(lds) + combine_bytes(p.group));
+    const LaneIds id(reinterpret_cast<char*>(lds));
     Item it;
     const int item = blockIdx.x;
     it.kvh = item % p.hkv;
@@ -525,6 +527,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_mfma_grid_kernel(DecodePar
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
     run_item<false>(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, [] {}, [] {});
+    __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
     combine_and_store(p, it, lds, p.group);
@@ -778,6 +781,10 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
 
 size_t lds_bytes(int group, bool persistent)
 {
+    if (!persistent) {
+        const size_t a = combine_bytes(group), b = (size_t)kWaves * kStageBytes;
+        return a > b ? a : b;
+    }
     return combine_bytes(group) + (size_t)kWaves * kStageBytes + (persistent ? 2 * (size_t)group * kD * 2 : 0);
 }
 
