@@ -175,6 +175,44 @@ omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head
                                 void* out_o, int32_t out_dtype, float* out_lse,
                                 void* hip_stream);
 
+/*
+ * KV-cache data movement around the decode step.
+ *
+ * The paper's decode context includes the token being decoded (its load is l_j + 1), so the new token's
+ * k, v are written into the paged cache before attention runs; and the KV cache of a request moves
+ * between GPU and CPU memory as a one-shot swap (KV cache management: swap-out overlapped with compute,
+ * delayed swap-in).  These three calls are the device side of both: pure copies, bit-exact.
+ */
+typedef struct {
+    int32_t batch, num_kv_heads, head_dim, block_size, max_blocks_per_seq;
+    int64_t num_blocks;
+    int32_t dtype;                 /* omni_dtype of the pools                                   */
+    void*   k_pool;                /* [num_blocks, num_kv_heads, block_size, head_dim], device  */
+    void*   v_pool;
+    const int32_t* block_table;    /* [batch, max_blocks_per_seq]; only omni_kv_append reads it  */
+} omni_kv_cache;
+
+/*
+ * Write k_new / v_new [batch, num_kv_heads, head_dim] (pool dtype, device) into the slot of logical
+ * token positions[i] (device int32 [batch]) of every sequence i: page block_table[i][pos/16], slot pos%16.
+ * A negative position, one past the table, or a table entry outside [0, num_blocks) writes nothing for
+ * that sequence.  Errors: NULL, SHAPE, DTYPE, UNSUPPORTED (block_size != 16, row bytes not a multiple of
+ * 16), LAUNCH.
+ */
+omni_status omni_kv_append(const omni_kv_cache* c, const void* k_new, const void* v_new,
+                           const int32_t* positions, void* hip_stream);
+
+/*
+ * Copy pages page_ids[0..n_pages) (device int32) of both pools to contiguous staging buffers
+ * k_out / v_out [n_pages, num_kv_heads, block_size, head_dim] (swap-out), or back from such buffers into
+ * the pools (swap-in).  A page id outside [0, num_blocks) reads as zeros / is skipped.  batch,
+ * max_blocks_per_seq and block_table of `c` are not used; n_pages = 0 does nothing.  Errors: NULL, SHAPE, DTYPE, UNSUPPORTED, LAUNCH.
+ */
+omni_status omni_kv_gather_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages,
+                                 void* k_out, void* v_out, void* hip_stream);
+omni_status omni_kv_scatter_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages,
+                                  const void* k_in, const void* v_in, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* omni_status_string(omni_status s);
 

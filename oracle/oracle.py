@@ -41,6 +41,10 @@ def _load():
         lib.oracle_merge.restype = None
         lib.oracle_gather_kv.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, vp]
         lib.oracle_gather_kv.restype = None
+        lib.oracle_kv_append.argtypes = [i32, i32, i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp]
+        lib.oracle_kv_append.restype = None
+        lib.oracle_kv_pages.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, i64, vp, vp, i32]
+        lib.oracle_kv_pages.restype = None
         _lib = lib
     return _lib
 
@@ -138,3 +142,41 @@ def gather_kv(k_pool, v_pool, block_table, seq: int, begin: int, end: int):
         lib.oracle_gather_kv(hkv, d, bs, bt.shape[1], k_pool.dtype.itemsize, _ptr(k_pool), _ptr(v_pool),
                              _ptr(bt), int(seq), int(begin), int(end), _ptr(k_out), _ptr(v_out))
     return k_out, v_out
+
+
+def kv_append(k_pool, v_pool, block_table, k_new, v_new, positions):
+    """In-place append of one token per sequence into writable pool arrays (see the C file)."""
+    lib = _load()
+    nb, hkv, bs, d = k_pool.shape
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    pos = np.ascontiguousarray(positions, dtype=np.int32)
+    for a in (k_pool, v_pool, k_new, v_new):
+        if not a.flags.c_contiguous or a.dtype != k_pool.dtype:
+            raise ValueError("contiguous arrays of one dtype expected")
+    if k_new.shape != (bt.shape[0], hkv, d) or v_new.shape != k_new.shape or pos.shape != (bt.shape[0],):
+        raise ValueError("bad shapes")
+    lib.oracle_kv_append(bt.shape[0], hkv, d, bs, bt.shape[1], nb, k_pool.dtype.itemsize, _ptr(k_pool), _ptr(v_pool),
+                         _ptr(bt), _ptr(k_new), _ptr(v_new), _ptr(pos))
+
+
+def kv_gather_pages(k_pool, v_pool, page_ids):
+    lib = _load()
+    nb, hkv, bs, d = k_pool.shape
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    k_out = np.empty((len(ids), hkv, bs, d), dtype=k_pool.dtype)
+    v_out = np.empty_like(k_out)
+    lib.oracle_kv_pages(hkv, d, bs, nb, k_pool.dtype.itemsize, _ptr(k_pool), _ptr(v_pool), _ptr(ids), len(ids),
+                        _ptr(k_out), _ptr(v_out), 0)
+    return k_out, v_out
+
+
+def kv_scatter_pages(k_pool, v_pool, page_ids, k_in, v_in):
+    lib = _load()
+    nb, hkv, bs, d = k_pool.shape
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    k_in = np.ascontiguousarray(k_in, dtype=k_pool.dtype)
+    v_in = np.ascontiguousarray(v_in, dtype=k_pool.dtype)
+    if k_in.shape != (len(ids), hkv, bs, d) or v_in.shape != k_in.shape:
+        raise ValueError("bad staging shape")
+    lib.oracle_kv_pages(hkv, d, bs, nb, k_pool.dtype.itemsize, _ptr(k_pool), _ptr(v_pool), _ptr(ids), len(ids),
+                        _ptr(k_in), _ptr(v_in), 1)

@@ -183,3 +183,58 @@ void oracle_gather_kv(int hkv, int d, int bs, int max_blocks, int elem_bytes,
             memcpy((char *)v_out + dst, (const char *)v_pool + (size_t)src * elem_bytes, row);
         }
 }
+
+/*
+ * KV-cache data movement (plain copies).  The decode context counts the token being decoded (latency-
+ * model section: l_j + 1), so its k, v enter the paged cache before attention; a request's KV moves
+ * between GPU and CPU memory as whole pages (KV cache management).
+ *
+ * oracle_kv_append: row (seq i, kv head h) of k_new/v_new [batch, hkv, d] goes to page
+ * block_table[i][pos/bs], slot pos%bs, pos = positions[i]; nothing is written for a position outside
+ * [0, max_blocks*bs) or a table entry outside [0, num_blocks).
+ */
+void oracle_kv_append(int batch, int hkv, int d, int bs, int max_blocks, int64_t num_blocks, int elem_bytes,
+                      void *k_pool, void *v_pool, const int32_t *block_table,
+                      const void *k_new, const void *v_new, const int32_t *positions)
+{
+    size_t row = (size_t)d * (size_t)elem_bytes;
+    for (int i = 0; i < batch; ++i) {
+        int pos = positions[i];
+        if (pos < 0 || pos / bs >= max_blocks) continue;
+        int64_t page = block_table[(int64_t)i * max_blocks + pos / bs];
+        if (page < 0 || page >= num_blocks) continue;
+        for (int h = 0; h < hkv; ++h) {
+            size_t dst = ((size_t)((page * hkv + h) * bs + pos % bs)) * row;
+            size_t src = ((size_t)i * hkv + h) * row;
+            memcpy((char *)k_pool + dst, (const char *)k_new + src, row);
+            memcpy((char *)v_pool + dst, (const char *)v_new + src, row);
+        }
+    }
+}
+
+/*
+ * oracle_kv_pages: to_pool = 0 copies pages page_ids[0..n) of both pools into staging buffers
+ * [n, hkv, bs, d] (ids outside [0, num_blocks) give zero pages); to_pool = 1 copies the staging pages
+ * back into the pools (such ids are skipped).
+ */
+void oracle_kv_pages(int hkv, int d, int bs, int64_t num_blocks, int elem_bytes, void *k_pool, void *v_pool,
+                     const int32_t *page_ids, int64_t n, void *k_stage, void *v_stage, int to_pool)
+{
+    size_t page_bytes = (size_t)hkv * bs * d * elem_bytes;
+    for (int64_t s = 0; s < n; ++s) {
+        int64_t page = page_ids[s];
+        int ok = page >= 0 && page < num_blocks;
+        char *ks = (char *)k_stage + (size_t)s * page_bytes, *vs = (char *)v_stage + (size_t)s * page_bytes;
+        if (to_pool) {
+            if (!ok) continue;
+            memcpy((char *)k_pool + (size_t)page * page_bytes, ks, page_bytes);
+            memcpy((char *)v_pool + (size_t)page * page_bytes, vs, page_bytes);
+        } else if (ok) {
+            memcpy(ks, (char *)k_pool + (size_t)page * page_bytes, page_bytes);
+            memcpy(vs, (char *)v_pool + (size_t)page * page_bytes, page_bytes);
+        } else {
+            memset(ks, 0, page_bytes);
+            memset(vs, 0, page_bytes);
+        }
+    }
+}

@@ -21,7 +21,8 @@ OMNI_KERNEL_AUTO, OMNI_KERNEL_VECTOR, OMNI_KERNEL_MFMA = 0, 1, 2
 OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OMNI_ERR_LAUNCH = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
-           "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy")
+           "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
+           "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages")
 
 
 class OmniError(RuntimeError):
@@ -44,6 +45,13 @@ class omni_decode_args(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_uint64),
         ("workspace_planned", ctypes.c_int32),
     ]
+
+
+class omni_kv_cache(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+                ("num_blocks", ctypes.c_int64), ("dtype", ctypes.c_int32),
+                ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("block_table", ctypes.c_void_p)]
 
 
 class omni_partial_src(ctypes.Structure):
@@ -81,6 +89,13 @@ def load_library() -> ctypes.CDLL:
         lib.omni_debug_stream_read.restype = ctypes.c_int
         lib.omni_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.omni_debug_copy.restype = ctypes.c_int
+        kvp = ctypes.POINTER(omni_kv_cache)
+        lib.omni_kv_append.argtypes = [kvp, vp, vp, vp, vp]
+        lib.omni_kv_append.restype = ctypes.c_int
+        lib.omni_kv_gather_pages.argtypes = [kvp, vp, ctypes.c_int64, vp, vp, vp]
+        lib.omni_kv_gather_pages.restype = ctypes.c_int
+        lib.omni_kv_scatter_pages.argtypes = [kvp, vp, ctypes.c_int64, vp, vp, vp]
+        lib.omni_kv_scatter_pages.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -247,3 +262,53 @@ def omni_debug_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> int:
     if st != OMNI_OK:
         raise OmniError(st, "omni_debug_copy")
     return st
+
+
+def make_kv_cache(k_pool, v_pool, block_table=None) -> omni_kv_cache:
+    c = omni_kv_cache()
+    c.num_blocks, c.num_kv_heads, c.block_size, c.head_dim = k_pool.shape
+    if tuple(v_pool.shape) != tuple(k_pool.shape) or v_pool.dtype != k_pool.dtype:
+        raise ValueError("k_pool and v_pool must match")
+    c.dtype = _dtype_code(k_pool, "k_pool")
+    c.k_pool, c.v_pool = _dev_ptr(k_pool, "k_pool"), _dev_ptr(v_pool, "v_pool")
+    if block_table is not None:
+        c.batch, c.max_blocks_per_seq = block_table.shape
+        c.block_table = _dev_ptr(block_table, "block_table", torch.int32)
+    return c
+
+
+def omni_kv_append(k_pool, v_pool, block_table, k_new, v_new, positions, stream=None, check: bool = True) -> int:
+    c = make_kv_cache(k_pool, v_pool, block_table)
+    want = (c.batch, c.num_kv_heads, c.head_dim)
+    if tuple(k_new.shape) != want or tuple(v_new.shape) != want or k_new.dtype != k_pool.dtype or v_new.dtype != k_pool.dtype:
+        raise ValueError("k_new / v_new must be [batch, num_kv_heads, head_dim] of the pool dtype")
+    if positions.numel() != c.batch:
+        raise ValueError("positions must have one entry per sequence")
+    st = load_library().omni_kv_append(ctypes.byref(c), _dev_ptr(k_new, "k_new"), _dev_ptr(v_new, "v_new"),
+                                       _dev_ptr(positions, "positions", torch.int32), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_kv_append")
+    return st
+
+
+def _kv_pages(fn_name, k_pool, v_pool, page_ids, k_stage, v_stage, stream, check):
+    c = make_kv_cache(k_pool, v_pool)
+    n = page_ids.numel()
+    per_page = c.num_kv_heads * c.block_size * c.head_dim
+    for t, name in ((k_stage, "k staging"), (v_stage, "v staging")):
+        if t.numel() != n * per_page or t.dtype != k_pool.dtype:
+            raise ValueError("%s must hold n_pages pages of the pool dtype" % name)
+    st = getattr(load_library(), fn_name)(ctypes.byref(c), _dev_ptr(page_ids, "page_ids", torch.int32), n,
+                                          _dev_ptr(k_stage, "k staging"), _dev_ptr(v_stage, "v staging"),
+                                          _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, fn_name)
+    return st
+
+
+def omni_kv_gather_pages(k_pool, v_pool, page_ids, k_out, v_out, stream=None, check: bool = True) -> int:
+    return _kv_pages("omni_kv_gather_pages", k_pool, v_pool, page_ids, k_out, v_out, stream, check)
+
+
+def omni_kv_scatter_pages(k_pool, v_pool, page_ids, k_in, v_in, stream=None, check: bool = True) -> int:
+    return _kv_pages("omni_kv_scatter_pages", k_pool, v_pool, page_ids, k_in, v_in, stream, check)

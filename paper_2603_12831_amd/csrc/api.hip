@@ -114,6 +114,58 @@ omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
 
+static omni_status flatten_kv(const omni_kv_cache* c, KvParams& k, bool need_table)
+{
+    if (!c) return OMNI_ERR_NULL;
+    if (c->num_kv_heads <= 0 || c->head_dim <= 0 || c->block_size <= 0 || c->num_blocks <= 0) return OMNI_ERR_SHAPE;
+    if (need_table && (c->batch < 0 || c->max_blocks_per_seq <= 0)) return OMNI_ERR_SHAPE;
+    if (!dtype_ok(c->dtype)) return OMNI_ERR_DTYPE;
+    if (c->block_size != kBlockSize) return OMNI_ERR_UNSUPPORTED;
+    const int eb = c->dtype == OMNI_BF16 ? 2 : 4;
+    if ((c->head_dim * eb) % 16 != 0) return OMNI_ERR_UNSUPPORTED;
+    if (!c->k_pool || !c->v_pool || (need_table && !c->block_table)) return OMNI_ERR_NULL;
+    k.batch = c->batch; k.hkv = c->num_kv_heads; k.d = c->head_dim; k.max_blocks = c->max_blocks_per_seq;
+    k.elem_bytes = eb; k.num_blocks = c->num_blocks; k.k_pool = c->k_pool; k.v_pool = c->v_pool;
+    k.block_table = c->block_table;
+    return OMNI_OK;
+}
+
+omni_status omni_kv_append(const omni_kv_cache* c, const void* k_new, const void* v_new,
+                           const int32_t* positions, void* hip_stream)
+{
+    KvParams k;
+    omni_status st = flatten_kv(c, k, true);
+    if (st != OMNI_OK) return st;
+    if (!k_new || !v_new || !positions) return OMNI_ERR_NULL;
+    hipError_t e = launch_kv_append(k, k_new, v_new, positions, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+static omni_status kv_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages, void* ks, void* vs,
+                            bool to_pool, void* hip_stream)
+{
+    KvParams k;
+    omni_status st = flatten_kv(c, k, false);
+    if (st != OMNI_OK) return st;
+    if (n_pages < 0) return OMNI_ERR_SHAPE;
+    if (n_pages == 0) return OMNI_OK;
+    if (!page_ids || !ks || !vs) return OMNI_ERR_NULL;
+    hipError_t e = launch_kv_pages(k, page_ids, n_pages, ks, vs, to_pool, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_kv_gather_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages,
+                                 void* k_out, void* v_out, void* hip_stream)
+{
+    return kv_pages(c, page_ids, n_pages, k_out, v_out, false, hip_stream);
+}
+
+omni_status omni_kv_scatter_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages,
+                                  const void* k_in, const void* v_in, void* hip_stream)
+{
+    return kv_pages(c, page_ids, n_pages, const_cast<void*>(k_in), const_cast<void*>(v_in), true, hip_stream);
+}
+
 const char* omni_status_string(omni_status s)
 {
     switch (s) {

@@ -33,6 +33,15 @@ struct DecodeParams {
     float* out_lse;                // may be null
 };
 
+// Flattened, validated form of omni_kv_cache.
+struct KvParams {
+    int batch, hkv, d, max_blocks, elem_bytes;
+    long long num_blocks;
+    void* k_pool;
+    void* v_pool;
+    const int* block_table;        // may be null for the page gather / scatter
+};
+
 struct MergeParams {
     omni_partial_src src[4];
     int n_srcs, batch, hq, d, out_bf16;
@@ -83,5 +92,8 @@ hipError_t launch_merge(const MergeParams& p, hipStream_t s);
 hipError_t launch_gather(const DecodeParams& p, bool bf16, int seq, void* k_out, void* v_out, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_kv_append(const KvParams& c, const void* k_new, const void* v_new, const int* positions, hipStream_t s);
+hipError_t launch_kv_pages(const KvParams& c, const int* page_ids, long long n_pages, void* k_stage, void* v_stage,
+                           bool to_pool, hipStream_t s);
 
 }  // namespace omni

@@ -103,3 +103,23 @@ def test_binding_refuses_host_tensors():
     end = torch.ones(1, dtype=torch.int32)
     with pytest.raises(ValueError):
         binding.omni_paged_decode_attn(q, kv, kv, bt, None, end, sm_scale=1.0, out_o=torch.zeros(1, 4, 64))
+
+
+def test_kv_cache_argument_errors():
+    lib = binding.load_library()
+    c = binding.omni_kv_cache()
+    c.batch, c.num_kv_heads, c.head_dim, c.block_size, c.max_blocks_per_seq, c.num_blocks = 2, 2, 64, 16, 4, 8
+    c.dtype, c.k_pool, c.v_pool, c.block_table = binding.OMNI_BF16, 0x1000, 0x1000, 0x1000
+    assert lib.omni_kv_append(None, 0x1000, 0x1000, 0x1000, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_kv_append(ctypes.byref(c), None, 0x1000, 0x1000, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_kv_gather_pages(ctypes.byref(c), None, 3, 0x1000, 0x1000, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_kv_gather_pages(ctypes.byref(c), 0x1000, -1, 0x1000, 0x1000, None) == binding.OMNI_ERR_SHAPE
+    assert lib.omni_kv_scatter_pages(ctypes.byref(c), 0x1000, 3, 0x1000, None, None) == binding.OMNI_ERR_NULL
+    c.block_size = 32
+    assert lib.omni_kv_append(ctypes.byref(c), 0x1000, 0x1000, 0x1000, None) == binding.OMNI_ERR_UNSUPPORTED
+    c.block_size, c.head_dim = 16, 4                                 # 8-byte rows cannot be moved in 16-byte pieces
+    assert lib.omni_kv_gather_pages(ctypes.byref(c), 0x1000, 3, 0x1000, 0x1000, None) == binding.OMNI_ERR_UNSUPPORTED
+    c.head_dim, c.dtype = 64, 9
+    assert lib.omni_kv_scatter_pages(ctypes.byref(c), 0x1000, 3, 0x1000, 0x1000, None) == binding.OMNI_ERR_DTYPE
+    c.dtype, c.block_table = binding.OMNI_F32, None
+    assert lib.omni_kv_append(ctypes.byref(c), 0x1000, 0x1000, 0x1000, None) == binding.OMNI_ERR_NULL
