@@ -125,7 +125,7 @@ def main() -> int:
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": step_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 inputs, f32 accumulate" if w.dtype == "bf16" else "f32",
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "accumulate_dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
                    "head_dim": w.head_dim, "page_tokens": w.block_size,

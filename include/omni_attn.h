@@ -213,6 +213,49 @@ omni_status omni_kv_gather_pages(const omni_kv_cache* c, const int32_t* page_ids
 omni_status omni_kv_scatter_pages(const omni_kv_cache* c, const int32_t* page_ids, int64_t n_pages,
                                   const void* k_in, const void* v_in, void* hip_stream);
 
+/*
+ * Device-resident row queues and residual store (System Implementation: "CPU Attention queue" — the
+ * input queue of q, k, v rows and the output queue of attention-result rows are tensors in GPU memory with
+ * head and tail pointers, producer at the tail, consumer at the head; "Residual management" — a store
+ * indexed by request and layer keeps the residual while the request's attention is computed elsewhere).
+ * GPU-side operations only; all pointers are device memory, counts stay on the device.
+ *
+ * A queue is a ring of `capacity` rows of `row_bytes` bytes (a multiple of 16), an optional int32 tag per
+ * row (e.g. the request id) and four uint32 state words {head, tail, 0, 0} that the caller zeroes once:
+ * head / tail count rows popped / pushed since then, a row with count c lives in slot c % capacity.
+ * Calls on one queue must be ordered (same stream).
+ */
+typedef struct {
+    void*     data;                /* [capacity, row_bytes]                                      */
+    int32_t*  tags;                /* [capacity] or NULL                                         */
+    uint32_t* state;               /* [4]                                                        */
+    int32_t   capacity, row_bytes;
+} omni_queue;
+
+/*
+ * Push n_rows rows (rows [n_rows, row_bytes], tags [n_rows] or NULL) at the tail — all of them, or, if
+ * they do not all fit, none; *n_pushed (device int32, may be NULL) receives n_rows or 0.
+ * Errors: NULL, SHAPE (capacity, row_bytes, n_rows), LAUNCH.
+ */
+omni_status omni_queue_push(const omni_queue* q, const void* rows, const int32_t* tags, int32_t n_rows,
+                            int32_t* n_pushed, void* hip_stream);
+/*
+ * Pop up to max_rows rows from the head into rows_out [max_rows, row_bytes] (tags into tags_out, may be
+ * NULL), oldest first; *n_popped (device int32, may be NULL) receives how many.
+ */
+omni_status omni_queue_pop(const omni_queue* q, void* rows_out, int32_t* tags_out, int32_t max_rows,
+                           int32_t* n_popped, void* hip_stream);
+
+/*
+ * Residual store [n_slots, row_bytes]: save rows [n_rows, row_bytes] to slots slot_ids[r] (the caller
+ * maps (request, layer) to a slot), or load those slots into rows.  Slot ids outside [0, n_slots) are
+ * skipped on save and give zero rows on load.  Errors: NULL, SHAPE, LAUNCH.
+ */
+omni_status omni_residual_save(void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids,
+                               int32_t n_rows, const void* rows, void* hip_stream);
+omni_status omni_residual_load(const void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids,
+                               int32_t n_rows, void* rows_out, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* omni_status_string(omni_status s);
 

@@ -41,6 +41,12 @@ def _load():
         lib.oracle_merge.restype = None
         lib.oracle_gather_kv.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, vp]
         lib.oracle_gather_kv.restype = None
+        lib.oracle_queue_push.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32]
+        lib.oracle_queue_push.restype = i32
+        lib.oracle_queue_pop.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32]
+        lib.oracle_queue_pop.restype = i32
+        lib.oracle_store_rows.argtypes = [vp, i64, i32, vp, i32, vp, i32]
+        lib.oracle_store_rows.restype = None
         lib.oracle_kv_append.argtypes = [i32, i32, i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp]
         lib.oracle_kv_append.restype = None
         lib.oracle_kv_pages.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, i64, vp, vp, i32]
@@ -180,3 +186,38 @@ def kv_scatter_pages(k_pool, v_pool, page_ids, k_in, v_in):
         raise ValueError("bad staging shape")
     lib.oracle_kv_pages(hkv, d, bs, nb, k_pool.dtype.itemsize, _ptr(k_pool), _ptr(v_pool), _ptr(ids), len(ids),
                         _ptr(k_in), _ptr(v_in), 1)
+
+
+class Queue:
+    """Host model of a row queue: ring [capacity, row_bytes] uint8, int32 tags, uint32 state words."""
+
+    def __init__(self, capacity: int, row_bytes: int):
+        self.data = np.zeros((capacity, row_bytes), dtype=np.uint8)
+        self.tags = np.zeros(capacity, dtype=np.int32)
+        self.state = np.zeros(4, dtype=np.uint32)
+
+    def push(self, rows: np.ndarray, tags=None) -> int:
+        rows = np.ascontiguousarray(rows, dtype=np.uint8).reshape(-1, self.data.shape[1])
+        t = None if tags is None else np.ascontiguousarray(tags, dtype=np.int32)
+        return _load().oracle_queue_push(_ptr(self.data), _ptr(self.tags), _ptr(self.state), self.data.shape[0],
+                                         self.data.shape[1], _ptr(rows), None if t is None else _ptr(t), rows.shape[0])
+
+    def pop(self, max_rows: int):
+        rows = np.zeros((max_rows, self.data.shape[1]), dtype=np.uint8)
+        tags = np.zeros(max_rows, dtype=np.int32)
+        n = _load().oracle_queue_pop(_ptr(self.data), _ptr(self.tags), _ptr(self.state), self.data.shape[0],
+                                     self.data.shape[1], _ptr(rows), _ptr(tags), max_rows)
+        return rows[:n], tags[:n]
+
+
+def store_save(store: np.ndarray, slot_ids, rows: np.ndarray):
+    ids = np.ascontiguousarray(slot_ids, dtype=np.int32)
+    rows = np.ascontiguousarray(rows, dtype=np.uint8).reshape(len(ids), store.shape[1])
+    _load().oracle_store_rows(_ptr(store), store.shape[0], store.shape[1], _ptr(ids), len(ids), _ptr(rows), 1)
+
+
+def store_load(store: np.ndarray, slot_ids) -> np.ndarray:
+    ids = np.ascontiguousarray(slot_ids, dtype=np.int32)
+    rows = np.empty((len(ids), store.shape[1]), dtype=np.uint8)
+    _load().oracle_store_rows(_ptr(store), store.shape[0], store.shape[1], _ptr(ids), len(ids), _ptr(rows), 0)
+    return rows

@@ -238,3 +238,56 @@ void oracle_kv_pages(int hkv, int d, int bs, int64_t num_blocks, int elem_bytes,
         }
     }
 }
+
+/*
+ * Row queues and residual store (System Implementation: CPU Attention queue, Residual management).
+ * A queue is a ring of `capacity` rows with head / tail counters in state[0] / state[1]; counter value c
+ * lives in slot c % capacity.  Push appends all n rows at the tail or, if they do not all fit, none;
+ * pop takes up to max_rows rows from the head, oldest first.  Both return the number of rows moved.
+ */
+int oracle_queue_push(void *data, int32_t *tags, uint32_t *state, int capacity, int row_bytes,
+                      const void *rows, const int32_t *row_tags, int n_rows)
+{
+    uint32_t head = state[0], tail = state[1];
+    if ((tail - head) + (uint32_t)n_rows > (uint32_t)capacity) return 0;
+    for (int r = 0; r < n_rows; ++r) {
+        uint32_t slot = (tail + (uint32_t)r) % (uint32_t)capacity;
+        memcpy((char *)data + (size_t)slot * row_bytes, (const char *)rows + (size_t)r * row_bytes, (size_t)row_bytes);
+        if (tags) tags[slot] = row_tags ? row_tags[r] : 0;
+    }
+    state[1] = tail + (uint32_t)n_rows;
+    return n_rows;
+}
+
+int oracle_queue_pop(const void *data, const int32_t *tags, uint32_t *state, int capacity, int row_bytes,
+                     void *rows_out, int32_t *tags_out, int max_rows)
+{
+    uint32_t head = state[0], tail = state[1];
+    uint32_t n = tail - head;
+    if (n > (uint32_t)max_rows) n = (uint32_t)max_rows;
+    for (uint32_t r = 0; r < n; ++r) {
+        uint32_t slot = (head + r) % (uint32_t)capacity;
+        memcpy((char *)rows_out + (size_t)r * row_bytes, (const char *)data + (size_t)slot * row_bytes, (size_t)row_bytes);
+        if (tags_out) tags_out[r] = tags ? tags[slot] : 0;
+    }
+    state[0] = head + n;
+    return (int)n;
+}
+
+/* Residual store: rows to / from slots slot_ids[r]; ids outside [0, n_slots) are skipped / read as zero. */
+void oracle_store_rows(void *store, int64_t n_slots, int row_bytes, const int32_t *slot_ids, int n_rows,
+                       void *rows, int save)
+{
+    for (int r = 0; r < n_rows; ++r) {
+        int64_t slot = slot_ids[r];
+        int ok = slot >= 0 && slot < n_slots;
+        char *row = (char *)rows + (size_t)r * row_bytes;
+        if (save) {
+            if (ok) memcpy((char *)store + (size_t)slot * row_bytes, row, (size_t)row_bytes);
+        } else if (ok) {
+            memcpy(row, (char *)store + (size_t)slot * row_bytes, (size_t)row_bytes);
+        } else {
+            memset(row, 0, (size_t)row_bytes);
+        }
+    }
+}

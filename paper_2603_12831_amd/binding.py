@@ -22,7 +22,8 @@ OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OM
 
 EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
-           "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages")
+           "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
+           "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load")
 
 
 class OmniError(RuntimeError):
@@ -52,6 +53,11 @@ class omni_kv_cache(ctypes.Structure):
                 ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
                 ("num_blocks", ctypes.c_int64), ("dtype", ctypes.c_int32),
                 ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("block_table", ctypes.c_void_p)]
+
+
+class omni_queue(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("tags", ctypes.c_void_p), ("state", ctypes.c_void_p),
+                ("capacity", ctypes.c_int32), ("row_bytes", ctypes.c_int32)]
 
 
 class omni_partial_src(ctypes.Structure):
@@ -89,6 +95,15 @@ def load_library() -> ctypes.CDLL:
         lib.omni_debug_stream_read.restype = ctypes.c_int
         lib.omni_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.omni_debug_copy.restype = ctypes.c_int
+        qp = ctypes.POINTER(omni_queue)
+        lib.omni_queue_push.argtypes = [qp, vp, vp, ctypes.c_int32, vp, vp]
+        lib.omni_queue_push.restype = ctypes.c_int
+        lib.omni_queue_pop.argtypes = [qp, vp, vp, ctypes.c_int32, vp, vp]
+        lib.omni_queue_pop.restype = ctypes.c_int
+        lib.omni_residual_save.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
+        lib.omni_residual_save.restype = ctypes.c_int
+        lib.omni_residual_load.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
+        lib.omni_residual_load.restype = ctypes.c_int
         kvp = ctypes.POINTER(omni_kv_cache)
         lib.omni_kv_append.argtypes = [kvp, vp, vp, vp, vp]
         lib.omni_kv_append.restype = ctypes.c_int
@@ -312,3 +327,58 @@ def omni_kv_gather_pages(k_pool, v_pool, page_ids, k_out, v_out, stream=None, ch
 
 def omni_kv_scatter_pages(k_pool, v_pool, page_ids, k_in, v_in, stream=None, check: bool = True) -> int:
     return _kv_pages("omni_kv_scatter_pages", k_pool, v_pool, page_ids, k_in, v_in, stream, check)
+
+
+def make_queue(data, tags, state) -> omni_queue:
+    """data: [capacity, row_bytes] uint8; tags: [capacity] int32 or None; state: [4] int32 (zeroed once)."""
+    q = omni_queue()
+    if data.dtype != torch.uint8 or data.dim() != 2 or state.numel() != 4 or state.element_size() != 4:
+        raise ValueError("queue data must be a 2-D uint8 tensor and state four 32-bit words")
+    q.capacity, q.row_bytes = data.shape
+    q.data, q.state = _dev_ptr(data, "queue data"), _dev_ptr(state, "queue state")
+    q.tags = _dev_ptr(tags, "queue tags", torch.int32)
+    return q
+
+
+def omni_queue_push(q: omni_queue, rows, tags=None, n_pushed=None, stream=None, check: bool = True) -> int:
+    n = rows.shape[0]
+    if rows.numel() * rows.element_size() != n * q.row_bytes or (tags is not None and tags.numel() != n):
+        raise ValueError("rows / tags do not match the queue's row size")
+    st = load_library().omni_queue_push(ctypes.byref(q), _dev_ptr(rows, "rows"), _dev_ptr(tags, "tags", torch.int32), n,
+                                        _dev_ptr(n_pushed, "n_pushed", torch.int32), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_queue_push")
+    return st
+
+
+def omni_queue_pop(q: omni_queue, rows_out, tags_out=None, n_popped=None, stream=None, check: bool = True) -> int:
+    n = rows_out.shape[0]
+    if rows_out.numel() * rows_out.element_size() != n * q.row_bytes or (tags_out is not None and tags_out.numel() != n):
+        raise ValueError("rows_out / tags_out do not match the queue's row size")
+    st = load_library().omni_queue_pop(ctypes.byref(q), _dev_ptr(rows_out, "rows_out"),
+                                       _dev_ptr(tags_out, "tags_out", torch.int32), n,
+                                       _dev_ptr(n_popped, "n_popped", torch.int32), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_queue_pop")
+    return st
+
+
+def _residual(fn_name, store, slot_ids, rows, stream, check):
+    n = slot_ids.numel()
+    row_bytes = store.shape[1] * store.element_size()
+    if store.dim() != 2 or rows.numel() * rows.element_size() != n * row_bytes:
+        raise ValueError("store must be [n_slots, row] and rows hold one store row per slot id")
+    st = getattr(load_library(), fn_name)(_dev_ptr(store, "store"), store.shape[0], row_bytes,
+                                          _dev_ptr(slot_ids, "slot_ids", torch.int32), n, _dev_ptr(rows, "rows"),
+                                          _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, fn_name)
+    return st
+
+
+def omni_residual_save(store, slot_ids, rows, stream=None, check: bool = True) -> int:
+    return _residual("omni_residual_save", store, slot_ids, rows, stream, check)
+
+
+def omni_residual_load(store, slot_ids, rows_out, stream=None, check: bool = True) -> int:
+    return _residual("omni_residual_load", store, slot_ids, rows_out, stream, check)

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libomni_attn.so")
-SOURCES = ["api.hip", "decode_vector.hip", "decode_mfma.hip", "merge.hip", "debug.hip", "kv_cache.hip"]
+SOURCES = ["api.hip", "decode_vector.hip", "decode_mfma.hip", "merge.hip", "debug.hip", "kv_cache.hip", "queues.hip"]
 
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -166,6 +166,59 @@ omni_status omni_kv_scatter_pages(const omni_kv_cache* c, const int32_t* page_id
     return kv_pages(c, page_ids, n_pages, const_cast<void*>(k_in), const_cast<void*>(v_in), true, hip_stream);
 }
 
+static omni_status flatten_queue(const omni_queue* q, QueueParams& k, int32_t n_rows)
+{
+    if (!q) return OMNI_ERR_NULL;
+    if (q->capacity <= 0 || q->row_bytes <= 0 || q->row_bytes % 16 != 0 || n_rows < 0) return OMNI_ERR_SHAPE;
+    if (!q->data || !q->state) return OMNI_ERR_NULL;
+    k.data = q->data; k.tags = q->tags; k.state = q->state; k.capacity = q->capacity; k.row_bytes = q->row_bytes;
+    return OMNI_OK;
+}
+
+omni_status omni_queue_push(const omni_queue* q, const void* rows, const int32_t* tags, int32_t n_rows,
+                            int32_t* n_pushed, void* hip_stream)
+{
+    QueueParams k;
+    omni_status st = flatten_queue(q, k, n_rows);
+    if (st != OMNI_OK) return st;
+    if (n_rows > 0 && !rows) return OMNI_ERR_NULL;
+    hipError_t e = launch_queue(k, true, rows, tags, nullptr, nullptr, n_rows, n_pushed, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_queue_pop(const omni_queue* q, void* rows_out, int32_t* tags_out, int32_t max_rows,
+                           int32_t* n_popped, void* hip_stream)
+{
+    QueueParams k;
+    omni_status st = flatten_queue(q, k, max_rows);
+    if (st != OMNI_OK) return st;
+    if (max_rows > 0 && !rows_out) return OMNI_ERR_NULL;
+    hipError_t e = launch_queue(k, false, nullptr, nullptr, rows_out, tags_out, max_rows, n_popped, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+static omni_status residual(void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids, int32_t n_rows,
+                            void* rows, bool save, void* hip_stream)
+{
+    if (n_slots <= 0 || row_bytes <= 0 || row_bytes % 16 != 0 || n_rows < 0) return OMNI_ERR_SHAPE;
+    if (n_rows == 0) return OMNI_OK;
+    if (!store || !slot_ids || !rows) return OMNI_ERR_NULL;
+    hipError_t e = launch_store(store, n_slots, row_bytes, slot_ids, n_rows, rows, save, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+omni_status omni_residual_save(void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids,
+                               int32_t n_rows, const void* rows, void* hip_stream)
+{
+    return residual(store, n_slots, row_bytes, slot_ids, n_rows, const_cast<void*>(rows), true, hip_stream);
+}
+
+omni_status omni_residual_load(const void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids,
+                               int32_t n_rows, void* rows_out, void* hip_stream)
+{
+    return residual(const_cast<void*>(store), n_slots, row_bytes, slot_ids, n_rows, rows_out, false, hip_stream);
+}
+
 const char* omni_status_string(omni_status s)
 {
     switch (s) {

@@ -656,7 +656,14 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     const WorkEntry w = entries[ticket / (unsigned)p.hkv];
     Item it;
     it.kvh = (int)(ticket % (unsigned)p.hkv);
-    it.seq = w.seq; it.chunk = w.chunk; it.cb = w.cb; it.ce = w.ce;
+    // A list that was planned for these very ranges holds only values that pass unchanged; one reused
+    // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are the
+    // worst that can come of it, never an access outside the table or the output buffers.
+    const int cap = p.max_blocks * kBlockSize;
+    it.seq = min(max(w.seq, 0), p.batch - 1);
+    it.chunk = min(max(w.chunk, 0), p.max_chunks - 1);
+    it.cb = min(max(w.cb, 0), cap - 1);
+    it.ce = min(max(w.ce, it.cb + 1), cap);
     finish_item(it, block_table, p.max_blocks);
     return it;
 }
@@ -671,16 +678,17 @@ __device__ __forceinline__ void persistent_body(
     char* const q_base = stage_base + kWaves * kStageBytes;          // two buffers of G rows, by item parity
     const int q_bytes = p.group * kD * 2;
     const LaneIds id(stage_base);
-    const unsigned n_tickets = counts[0] * (unsigned)p.hkv;
+    const unsigned n_tickets = min(counts[0], (unsigned)(p.batch * p.max_chunks)) * (unsigned)p.hkv;
     const float scale2 = p.sm_scale * kLog2e;
 
     // rows of empty chunks: LSE = -inf (stores only, shared out over the resident workgroups)
     {
-        const unsigned n_empty = counts[1];
         const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
+        const unsigned n_empty = min(counts[1], last + 1u);
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
             const WorkEntry w = entries[last - i];
-            store_empty(p, w.seq, w.chunk, 0, p.hq, threadIdx.x, kThreads);
+            store_empty(p, min(max(w.seq, 0), p.batch - 1), min(max(w.chunk, 0), p.max_chunks - 1), 0, p.hq,
+                        threadIdx.x, kThreads);
         }
     }
 

@@ -42,6 +42,14 @@ struct KvParams {
     const int* block_table;        // may be null for the page gather / scatter
 };
 
+// Flattened form of omni_queue.
+struct QueueParams {
+    void* data;
+    int* tags;                     // may be null
+    unsigned* state;               // head, tail, departed workgroups, unused
+    int capacity, row_bytes;
+};
+
 struct MergeParams {
     omni_partial_src src[4];
     int n_srcs, batch, hq, d, out_bf16;
@@ -92,6 +100,10 @@ hipError_t launch_merge(const MergeParams& p, hipStream_t s);
 hipError_t launch_gather(const DecodeParams& p, bool bf16, int seq, void* k_out, void* v_out, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_queue(const QueueParams& q, bool push, const void* src_rows, const int* src_tags, void* dst_rows,
+                        int* dst_tags, int n_rows, int* n_done, hipStream_t s);
+hipError_t launch_store(void* store, long long n_slots, int row_bytes, const int* slot_ids, int n_rows, void* rows,
+                        bool save, hipStream_t s);
 hipError_t launch_kv_append(const KvParams& c, const void* k_new, const void* v_new, const int* positions, hipStream_t s);
 hipError_t launch_kv_pages(const KvParams& c, const int* page_ids, long long n_pages, void* k_stage, void* v_stage,
                            bool to_pool, hipStream_t s);

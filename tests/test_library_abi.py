@@ -123,3 +123,21 @@ def test_kv_cache_argument_errors():
     assert lib.omni_kv_scatter_pages(ctypes.byref(c), 0x1000, 3, 0x1000, 0x1000, None) == binding.OMNI_ERR_DTYPE
     c.dtype, c.block_table = binding.OMNI_F32, None
     assert lib.omni_kv_append(ctypes.byref(c), 0x1000, 0x1000, 0x1000, None) == binding.OMNI_ERR_NULL
+
+
+def test_queue_and_store_argument_errors():
+    lib = binding.load_library()
+    q = binding.omni_queue()
+    q.data, q.state, q.capacity, q.row_bytes = 0x1000, 0x1000, 8, 64
+    assert lib.omni_queue_push(None, 0x1000, None, 1, None, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_queue_push(ctypes.byref(q), None, None, 2, None, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_queue_pop(ctypes.byref(q), None, None, 2, None, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_queue_push(ctypes.byref(q), 0x1000, None, -1, None, None) == binding.OMNI_ERR_SHAPE
+    q.row_bytes = 24
+    assert lib.omni_queue_pop(ctypes.byref(q), 0x1000, None, 2, None, None) == binding.OMNI_ERR_SHAPE
+    q.row_bytes, q.state = 64, None
+    assert lib.omni_queue_pop(ctypes.byref(q), 0x1000, None, 2, None, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_residual_save(0x1000, 0, 64, 0x1000, 2, 0x1000, None) == binding.OMNI_ERR_SHAPE
+    assert lib.omni_residual_save(0x1000, 4, 20, 0x1000, 2, 0x1000, None) == binding.OMNI_ERR_SHAPE
+    assert lib.omni_residual_load(None, 4, 64, 0x1000, 2, 0x1000, None) == binding.OMNI_ERR_NULL
+    assert lib.omni_residual_load(0x1000, 4, 64, 0x1000, 0, None, None) == binding.OMNI_OK
