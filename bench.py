@@ -56,7 +56,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--pools", type=int, default=2, help="physical KV pool copies rotated between steps")
     ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 vector, 2 matrix-core")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -79,7 +79,15 @@ def main() -> int:
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
 
     w = wl.MAKERS[args.workload](workers=cores)
-    dw = DeviceWorkload(w, n_pool_copies=max(1, args.pools))
+    ext = {}
+    if w.ext_ranges is not None:
+        # hybrid batch: the externally produced partial rows are stand-ins of the right shape and layout
+        # (seeded random values): only their traffic matters to the timing
+        off = wl.ext_row_offsets(w)
+        rng = np.random.default_rng(4)
+        ext = dict(ext_o=rng.standard_normal((int(off[-1]), w.num_q_heads, w.head_dim), dtype=np.float32),
+                   ext_lse=rng.standard_normal((int(off[-1]), w.num_q_heads), dtype=np.float32), ext_offsets=off)
+    dw = DeviceWorkload(w, n_pool_copies=max(1, args.pools), **ext)
     kv_bytes = w.kv_bytes()
     alg_bytes = algorithmic_bytes(w)
 
