@@ -575,9 +575,9 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 
 // Work list of a call: the non-empty (sequence, chunk) ranges, longest first, from the front of
 // `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
-// of non-empty entries, word 2 number of empty ones, words 3 and 4 counts of departed / arrived workgroups
-// (zeroed here).  Depends only on the ranges and the chunking, so a
-// list can serve every call that shares them (all layers of one decoding iteration).
+// of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here).
+// Depends only on the ranges and the chunking, so a list can serve every call that shares them (all
+// layers of one decoding iteration).
 constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
 
 __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsigned* __restrict__ header,
@@ -634,7 +634,6 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
             header[1] = incl;
             header[2] = hist[kSortBins];
             header[3] = 0;
-            header[4] = 0;
             hist[kSortBins] = 0;
         }
     }
@@ -682,7 +681,7 @@ __device__ __forceinline__ void persistent_body(
     const float scale2 = p.sm_scale * kLog2e;
 
     // rows of empty chunks: LSE = -inf (stores only, shared out over the resident workgroups)
-    {
+    auto store_empty_share = [&] {
         const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
         const unsigned n_empty = min(counts[1], last + 1u);
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
@@ -690,23 +689,22 @@ __device__ __forceinline__ void persistent_body(
             store_empty(p, min(max(w.seq, 0), p.batch - 1), min(max(w.chunk, 0), p.max_chunks - 1), 0, p.hq,
                         threadIdx.x, kThreads);
         }
-    }
+    };
 
-    // The first two tickets of a workgroup are fixed by its arrival number a among the N launched
-    // (all resident) workgroups: a and 2N-1-a.  With the list longest-first that pairs the longest items
-    // with the shortest of the first 2N, which is what a longest-first greedy assignment would do; tickets
-    // from 2N on are drawn one at a time as workgroups get to them.
+    // The first two tickets of a workgroup are fixed by its index a among the N launched (all resident)
+    // workgroups: a and 2N-1-a.  With the list longest-first that pairs the longest items with the
+    // shortest of the first 2N, which is what a longest-first greedy assignment would do; tickets from 2N
+    // on are drawn one at a time as workgroups get to them.
     const unsigned first_dynamic = 2u * gridDim.x;
-    if (threadIdx.x == 0) {
-        const unsigned a = atomicAdd(ticket_counter + 4, 1u);
-        sh_ticket[0] = a;
-        sh_ticket[1] = first_dynamic - 1u - a;
+    if (threadIdx.x == 0) sh_ticket[1] = first_dynamic - 1u - blockIdx.x;   // read after the first barrier
+    unsigned tk = blockIdx.x;
+    if (tk >= n_tickets) {
+        store_empty_share();
+        return;
     }
-    __syncthreads();
-    unsigned tk = __builtin_amdgcn_readfirstlane(sh_ticket[0]);
-    if (tk >= n_tickets) return;
 
-    // first item: wave 0 brings Q into LDS, every wave requests its first step, then all read Q
+    // first item: wave 0 brings Q into LDS, every wave requests its first step, then all read Q; the
+    // stores for the empty rows go out while those first loads are on their way
     Item it = ticket_item(p, entries, block_table, tk);
     if (id.wave == 0) issue_q(p, it, id.lane, q_base);
     StepRegs r;
@@ -715,6 +713,7 @@ __device__ __forceinline__ void persistent_body(
         cur = step_pages(p, it, id.wave);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
+    store_empty_share();
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
     u32x4 qb[4];
@@ -769,9 +768,8 @@ __device__ __forceinline__ void persistent_body(
     OMNI_WAIT_VMCNT(0);                                    // no direct-to-LDS load may outlive the workgroup
 }
 
-// Header words 0 (ticket counter), 3 (workgroups that have left) and 4 (workgroups that have arrived) are
-// the only mutable state of a work list; the last workgroup to leave puts them back to zero, so the same
-// list can serve the next call.
+// Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
+// list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
 __global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
@@ -781,7 +779,6 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
             atomicExch(header + 3, 0u);
-            atomicExch(header + 4, 0u);
             atomicExch(header, 0u);
         }
     }
@@ -842,8 +839,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
         e = launch_decode_plan(p, workspace, s);
         if (e != hipSuccess) return e;
     }
-    // exactly as many workgroups as are resident at once: the first two tickets of each are fixed by its
-    // arrival number, so none may have to wait for another to leave
+    // exactly as many workgroups as are resident at once: each keeps streaming from its first ticket to
+    // the end of the list, and the first two tickets of each are fixed by its index
     int per_cu = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kThreads, lds);
     if (e != hipSuccess) return e;
