@@ -65,7 +65,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kSortBins = 256;
 
-struct WorkEntry { int seq, chunk, cb, ce; };          // a non-empty token range [cb, ce) of one chunk
+struct alignas(16) WorkEntry { int seq, chunk, cb, ce; };   // a non-empty token range [cb, ce) of one chunk
 
 struct StepRegs {            // raw V registers of one 32-token step (pages A and B); K waits in LDS
     u32x4 va[4], vb[4];
@@ -83,6 +83,20 @@ struct Item {                // wave-uniform description of a work item
     int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
     const int* __restrict__ table;
 };
+
+// Data no kernel of a launch writes (block table, work list) is read through the constant address space:
+// a wave-uniform read then always becomes a scalar load, whatever else the kernel stores or updates.
+__device__ __forceinline__ int load_invariant(const int* ptr)
+{
+    return *(const __attribute__((address_space(4))) int*)ptr;
+}
+
+__device__ __forceinline__ WorkEntry load_invariant(const WorkEntry* ptr)
+{
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const i32x4 v = *(const __attribute__((address_space(4))) i32x4*)ptr;
+    return WorkEntry{v[0], v[1], v[2], v[3]};
+}
 
 struct Pages { long long a, b; };                      // physical pages of a step, -1 = absent
 
@@ -114,11 +128,11 @@ __device__ __forceinline__ Pages step_pages(const DecodeParams& p, const Item& i
     Pages r = {-1, -1};
     const int lp = __builtin_amdgcn_readfirstlane(it.lp_first + 2 * s);
     if (lp <= it.lp_last) {
-        long long pg = it.table[lp];
+        long long pg = load_invariant(it.table + lp);
         r.a = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
     }
     if (lp + 1 <= it.lp_last) {
-        long long pg = it.table[lp + 1];
+        long long pg = load_invariant(it.table + lp + 1);
         r.b = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
     }
     return r;
@@ -347,13 +361,14 @@ struct Tail {
 };
 
 // All steps of an item that belong to this wave.  On entry the loads of the wave's first step are
-// already requested (if it has one).  The wave's last step is peeled off: `before_last` runs right before
-// it and `after_last` right after, and during it the wave requests `tail` instead of a further step of
-// this item.
-template <bool chained, class Before, class After>
+// already requested (if it has one).  `at_penult(true)` runs right before and `at_penult(false)` right
+// after the wave's second-to-last step (if it has two or more).  The wave's last step is peeled off:
+// `before_last` runs right before it and returns what the wave requests during it instead of a further
+// step of this item, `after_last` runs right after it.
+template <bool chained, class Penult, class Before, class After>
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                          const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur,
-                                         const Tail& tail, Before&& before_last, After&& after_last)
+                                         Penult&& at_penult, Before&& before_last, After&& after_last)
 {
     int s = id.wave;
     Pages nxt = {-1, -1};
@@ -361,15 +376,18 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
     // everything older than the first step's 8 K + 8 V requests has landed
     OMNI_WAIT_VMCNT(16);
     while (s + kWaves < it.n_steps) {
+        const bool penult = s + 2 * kWaves >= it.n_steps;
         Pages nn = {-1, -1};
-        if (s + 2 * kWaves < it.n_steps) nn = step_pages(p, it, s + 2 * kWaves);   // table reads run a step ahead
+        if (!penult) nn = step_pages(p, it, s + 2 * kWaves);                       // table reads run a step ahead
+        else at_penult(true);
         attend_step<true>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2);
+        if (penult) at_penult(false);
         cur = nxt;
         nxt = nn;
         s += kWaves;
     }
     if (s < it.n_steps) {
-        before_last();
+        const Tail tail = before_last();
         // `chained`: the step always ends with a request (the next item's first step, or, when there is
         // none, a throw-away re-read of page 0), so that one copy of the step code with exact load
         // counts serves; a second copy for "nothing follows" cost registers to the point of spilling
@@ -388,6 +406,23 @@ __device__ __forceinline__ void lds_barrier()
     // moving LDS accesses across.  A fence would also wait for the direct-to-LDS loads in flight, which
     // only ever target the issuing wave's own staging area.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// A word in LDS that one thread posts and waves of the same workgroup poll between barriers.  Written
+// as instructions of their own: an LDS access the compiler knows of makes it wait first for every
+// direct-to-LDS load in flight (it cannot tell the staging areas from this word), which would drain the
+// wave's memory pipe at each poll.
+__device__ __forceinline__ unsigned lds_peek(const unsigned* word)
+{
+    const unsigned addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) unsigned*)word;
+    unsigned v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr));
+    return v;
+}
+__device__ __forceinline__ void lds_post(unsigned* word, unsigned value)
+{
+    const unsigned addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned*)word;
+    asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(value) : "memory");
 }
 
 // Q rows of an item's G heads into an LDS buffer ([g][256 bytes]) by one wave's direct-to-LDS loads:
@@ -526,7 +561,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
         cur = step_pages(p, it, id.wave);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
-    run_item<false>(p, it, st, r, qb, id, scale2, cur, Tail{false, 0, Pages{-1, -1}}, [] {}, [] {});
+    run_item<false>(p, it, st, r, qb, id, scale2, cur, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
     __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
@@ -652,7 +687,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
 __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
                                             const int* __restrict__ block_table, unsigned ticket)
 {
-    const WorkEntry w = entries[ticket / (unsigned)p.hkv];
+    const WorkEntry w = load_invariant(entries + ticket / (unsigned)p.hkv);
     Item it;
     it.kvh = (int)(ticket % (unsigned)p.hkv);
     // A list that was planned for these very ranges holds only values that pass unchanged; one reused
@@ -685,18 +720,26 @@ __device__ __forceinline__ void persistent_body(
         const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
         const unsigned n_empty = min(counts[1], last + 1u);
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
-            const WorkEntry w = entries[last - i];
+            const WorkEntry w = load_invariant(entries + (last - i));
             store_empty(p, min(max(w.seq, 0), p.batch - 1), min(max(w.chunk, 0), p.max_chunks - 1), 0, p.hq,
                         threadIdx.x, kThreads);
         }
     };
 
-    // The first two tickets of a workgroup are fixed by its index a among the N launched (all resident)
-    // workgroups: a and 2N-1-a.  With the list longest-first that pairs the longest items with the
-    // shortest of the first 2N, which is what a longest-first greedy assignment would do; tickets from 2N
-    // on are drawn one at a time as workgroups get to them.
-    const unsigned first_dynamic = 2u * gridDim.x;
-    if (threadIdx.x == 0) sh_ticket[1] = first_dynamic - 1u - blockIdx.x;   // read after the first barrier
+    // A workgroup's first item is fixed by its index; every further one is drawn from the ticket counter
+    // as late as the latencies allow, so that a workgroup that gets little of the memory bandwidth (the
+    // CU favours its oldest waves) does not sit on items claimed long ago while the others run dry.
+    // Slot j % 3 of sh_ticket holds the ticket of the workgroup's j-th item once thread 0 knows it
+    // (kPending before).  The ticket of item k+1 is drawn by thread 0 before its second-to-last step of
+    // item k and published after that step; if item k is too short for that (a single step per wave) it
+    // is drawn a whole item earlier, in the last step of item k-1 (for k = 0: at the start).  Every wave
+    // picks the ticket up right before its own last step of item k (waiting, if it got there first,
+    // for thread 0, which never waits for anybody between barriers), reads the item's description and
+    // first pages, and in that last step streams the first step of item k+1 instead of a further step
+    // of item k, so the memory pipe does not drain between items.
+    constexpr unsigned kPending = 0xffffffffu;
+    const unsigned first_dynamic = gridDim.x;
+    auto short_item = [](const Item& x) { return x.n_steps <= kWaves; };
     unsigned tk = blockIdx.x;
     if (tk >= n_tickets) {
         store_empty_share();
@@ -706,6 +749,11 @@ __device__ __forceinline__ void persistent_body(
     // first item: wave 0 brings Q into LDS, every wave requests its first step, then all read Q; the
     // stores for the empty rows go out while those first loads are on their way
     Item it = ticket_item(p, entries, block_table, tk);
+    if (threadIdx.x == 0) {
+        sh_ticket[0] = kPending;
+        sh_ticket[2] = kPending;
+        sh_ticket[1] = short_item(it) ? first_dynamic + atomicAdd(ticket_counter, 1u) : kPending;
+    }
     if (id.wave == 0) issue_q(p, it, id.lane, q_base);
     StepRegs r;
     Pages cur = {-1, -1};
@@ -722,31 +770,48 @@ __device__ __forceinline__ void persistent_body(
     st.reset();
 
     for (int k = 0;; ++k) {
-        // the next item's description and first pages are fetched while this item streams
-        const unsigned tn = __builtin_amdgcn_readfirstlane(sh_ticket[(k + 1) % 3]);
-        const bool has_next = tn < n_tickets;
+        unsigned* const slot_next = &sh_ticket[(k + 1) % 3];
+        char* const q_next = q_base + ((k + 1) & 1) * q_bytes;
+        const bool late_draw = !short_item(it);
+        const bool streamed = id.wave < it.n_steps;
         Item nx = it;
         Tail tail = {false, 0, Pages{-1, -1}};
-        if (has_next) {
-            nx = ticket_item(p, entries, block_table, tn);
-            if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
-        }
-        char* const q_next = q_base + ((k + 1) & 1) * q_bytes;
+        bool has_next = false;
+        unsigned t1 = 0, t2 = 0;
+        bool draw2 = false;
 
-        // Right before its last step of this item wave 0 requests the next item's Q (into the other Q
-        // buffer) and thread 0 draws the ticket of the item after next (late, so that tickets go to
-        // whoever gets there first); in the last step every wave streams the first step of the next item
-        // instead of a further step of this one.  Wave 0 has a step in every item.
-        unsigned t2 = 0;
-        const bool streamed = id.wave < it.n_steps;
-        run_item<true>(p, it, st, r, qb, id, scale2, cur, tail,
-                 [&] {
-                     if (has_next && id.wave == 0) issue_q(p, nx, id.lane, q_next);
-                     if (threadIdx.x == 0) t2 = atomicAdd(ticket_counter, 1u);
+        // the next item's ticket, description and first pages of this wave
+        auto acquire = [&] {
+            unsigned tn;
+            while ((tn = lds_peek(slot_next)) == kPending) __builtin_amdgcn_s_sleep(1);
+            tn = __builtin_amdgcn_readfirstlane(tn);
+            has_next = tn < n_tickets;
+            if (has_next) {
+                nx = ticket_item(p, entries, block_table, tn);
+                if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
+            }
+        };
+
+        run_item<true>(p, it, st, r, qb, id, scale2, cur,
+                 [&](bool before) {
+                     if (threadIdx.x == 0 && late_draw) {
+                         if (before) t1 = atomicAdd(ticket_counter, 1u);
+                         else lds_post(slot_next, first_dynamic + t1);
+                     }
                  },
                  [&] {
-                     if (threadIdx.x == 0) sh_ticket[(k + 2) % 3] = first_dynamic + t2;
+                     acquire();
+                     // wave 0 requests the next item's Q into the other Q buffer; a short next item has
+                     // no second-to-last step to draw its successor's ticket in: thread 0 draws it now
+                     if (has_next && id.wave == 0) issue_q(p, nx, id.lane, q_next);
+                     draw2 = has_next && short_item(nx);
+                     if (threadIdx.x == 0 && draw2) t2 = atomicAdd(ticket_counter, 1u);
+                     return tail;
+                 },
+                 [&] {
+                     if (threadIdx.x == 0 && draw2) lds_post(&sh_ticket[(k + 2) % 3], first_dynamic + t2);
                  });
+        if (!streamed) acquire();
 
         // accumulators go to LDS; waves that had no step in this item request their first step of the next
         // one now; wave 0 makes sure the next Q has landed (it is older than the 16 K/V requests behind
@@ -761,6 +826,7 @@ __device__ __forceinline__ void persistent_body(
         combine_and_store(p, it, lds, p.group);
         if (!has_next) break;
         lds_barrier();                                     // LDS is rewritten by the next item's staging
+        if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by item k+4
         read_q(q_next, p.group, id.col, id.kg, qb);
         st.reset();
         it = nx;
