@@ -334,6 +334,27 @@ def test_work_list_with_many_sequences():
     run_and_check(w, (binding.OMNI_KERNEL_AUTO, False))
 
 
+def test_ticket_handover_across_item_lengths():
+    """More items than resident workgroups, with lengths that put 1 to 10 steps of 32 tokens in an item
+    (a wave then has none, one, two or three steps of it) in every order: the hand-over from one item to
+    the next - ticket drawn early for single-step items, late otherwise, picked up by each wave on its
+    own - must serve every item exactly once.  Run twice on one work list."""
+    rng = np.random.default_rng(63)
+    pool = np.array([1, 16, 31, 33, 64, 65, 96, 128, 129, 160, 161, 192, 224, 256, 257, 288, 300, 320])
+    lengths = rng.choice(pool, size=440)
+    begin = rng.integers(0, 2, size=440) * rng.integers(0, 20, size=440)
+    w = wl.make_generic(63, lengths + begin, 8, 4, 128, dtype="bf16", ctx_begin=begin)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    (_, _), dw = run_and_check(w, BENCH_FORM, expected=exp)
+    dw.poison_outputs()
+    dw.run(kernel=BENCH_FORM[0])
+    got_o, got_l = dw.results()
+    check(got_o, got_l, exp[0], exp[1], TOL["bf16"], "second pass")
+    # same ranges cut into 64-token chunks: items of one and two steps only, several thousand of them
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 64, 6
+    run_and_check(w, BENCH_FORM, expected=exp)
+
+
 def test_workspace_too_small_is_rejected():
     w = wl.make_generic(63, [100, 50], 8, 2, 128, dtype="bf16", chunk_tokens=32)
     dw = DeviceWorkload(w, out_dtype="f32")
