@@ -256,6 +256,44 @@ omni_status omni_residual_save(void* store, int64_t n_slots, int32_t row_bytes, 
 omni_status omni_residual_load(const void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids,
                                int32_t n_rows, void* rows_out, void* hip_stream);
 
+/*
+ * Host-side producer of partial rows: attention over KV held in HOST memory, computed on the host's
+ * cores (the paper's System Implementation, "CPU Attention": threads across the cores each take a part
+ * of the load and the intermediate results are aggregated; the inner loops are vectorised).  It makes
+ * no GPU call.  Every pointer of this struct is HOST memory owned by the caller.
+ *
+ * Row r covers tokens [row_begin[r], row_end[r]) of sequence row_seq[r] (ranges clamped as for
+ * omni_paged_decode_attn; a page index outside [0, num_blocks) removes its 16 tokens) and yields, for
+ * every query head, the partial defined under "Partials" above: part_o[r][head][:] (fp32, normalised
+ * inside the range) and part_lse[r][head].  Rows listed sequence by sequence are a CSR source for
+ * omni_merge_partials once copied to the device.  An empty range writes LSE = -inf and O = 0.
+ * Layouts of q, the pools and the block table are those of omni_decode_args.  Arithmetic: products and
+ * sums in fp32, inputs fp32 or bf16.  The call returns when all rows are written; it runs n_threads
+ * threads of its own (0 = one per hardware thread) and allocates host scratch of
+ * (number of 512-token slices) x G x (head_dim + 2) floats.
+ * Errors: NULL, SHAPE (also a row_seq outside [0, batch)), DTYPE, UNSUPPORTED (block_size != 16,
+ * head_dim not 64 / 128, G > 16).  n_rows = 0 is OK and does nothing.
+ */
+typedef struct {
+    int32_t n_rows;
+    int32_t batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq;
+    int64_t num_blocks;
+    int32_t qkv_dtype;             /* omni_dtype of q, k_pool, v_pool */
+    float   sm_scale;
+    const void*    q;              /* [batch, num_q_heads, head_dim]                         */
+    const void*    k_pool;         /* [num_blocks, num_kv_heads, block_size, head_dim]       */
+    const void*    v_pool;
+    const int32_t* block_table;    /* [batch, max_blocks_per_seq]                            */
+    const int32_t* row_seq;        /* [n_rows]                                               */
+    const int32_t* row_begin;      /* [n_rows]; NULL = all zero                              */
+    const int32_t* row_end;        /* [n_rows]                                               */
+    float* part_o;                 /* [n_rows, num_q_heads, head_dim]                        */
+    float* part_lse;               /* [n_rows, num_q_heads]                                  */
+    int32_t n_threads;
+} omni_host_attn_args;
+
+omni_status omni_host_partial_attn(const omni_host_attn_args* a);
+
 /* Static, human-readable name of a status code. */
 const char* omni_status_string(omni_status s);
 

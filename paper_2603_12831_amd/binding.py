@@ -23,7 +23,8 @@ OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OM
 EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
-           "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load")
+           "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
+           "omni_host_partial_attn")
 
 
 class OmniError(RuntimeError):
@@ -58,6 +59,17 @@ class omni_kv_cache(ctypes.Structure):
 class omni_queue(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("tags", ctypes.c_void_p), ("state", ctypes.c_void_p),
                 ("capacity", ctypes.c_int32), ("row_bytes", ctypes.c_int32)]
+
+
+class omni_host_attn_args(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32),
+                ("batch", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+                ("num_blocks", ctypes.c_int64), ("qkv_dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+                ("q", ctypes.c_void_p), ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
+                ("block_table", ctypes.c_void_p), ("row_seq", ctypes.c_void_p), ("row_begin", ctypes.c_void_p),
+                ("row_end", ctypes.c_void_p), ("part_o", ctypes.c_void_p), ("part_lse", ctypes.c_void_p),
+                ("n_threads", ctypes.c_int32)]
 
 
 class omni_partial_src(ctypes.Structure):
@@ -111,6 +123,8 @@ def load_library() -> ctypes.CDLL:
         lib.omni_kv_gather_pages.restype = ctypes.c_int
         lib.omni_kv_scatter_pages.argtypes = [kvp, vp, ctypes.c_int64, vp, vp, vp]
         lib.omni_kv_scatter_pages.restype = ctypes.c_int
+        lib.omni_host_partial_attn.argtypes = [ctypes.POINTER(omni_host_attn_args)]
+        lib.omni_host_partial_attn.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -382,3 +396,37 @@ def omni_residual_save(store, slot_ids, rows, stream=None, check: bool = True) -
 
 def omni_residual_load(store, slot_ids, rows_out, stream=None, check: bool = True) -> int:
     return _residual("omni_residual_load", store, slot_ids, rows_out, stream, check)
+
+
+def omni_host_partial_attn(q, k_pool, v_pool, block_table, row_seq, row_begin, row_end, sm_scale: float,
+                           dtype: str, n_threads: int = 0, check: bool = True):
+    """Partial rows computed on the host's cores from KV in host memory.  q, k_pool, v_pool: C-contiguous
+    numpy arrays (float32, or uint16 holding bf16 bit patterns when dtype == "bf16") in the layouts of the
+    decode call; block_table int32 [batch, max_blocks]; row_seq / row_begin / row_end int32 [n_rows].
+    Returns (part_o [n_rows, Hq, D] float32, part_lse [n_rows, Hq] float32)."""
+    import numpy as np
+    want = np.uint16 if dtype == "bf16" else np.float32
+    for name, arr in (("q", q), ("k_pool", k_pool), ("v_pool", v_pool)):
+        if arr.dtype != want or not arr.flags["C_CONTIGUOUS"]:
+            raise ValueError("%s must be a C-contiguous %s array" % (name, np.dtype(want).name))
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    row_seq = np.ascontiguousarray(row_seq, dtype=np.int32)
+    row_end = np.ascontiguousarray(row_end, dtype=np.int32)
+    row_begin = None if row_begin is None else np.ascontiguousarray(row_begin, dtype=np.int32)
+    n_rows = int(row_seq.shape[0])
+    batch, hq, d = q.shape
+    num_blocks, hkv, bs, _ = k_pool.shape
+    part_o = np.empty((n_rows, hq, d), dtype=np.float32)
+    part_lse = np.empty((n_rows, hq), dtype=np.float32)
+    a = omni_host_attn_args(
+        n_rows=n_rows, batch=batch, num_q_heads=hq, num_kv_heads=hkv, head_dim=d, block_size=bs,
+        max_blocks_per_seq=block_table.shape[1], num_blocks=num_blocks,
+        qkv_dtype=OMNI_BF16 if dtype == "bf16" else OMNI_F32, sm_scale=float(sm_scale),
+        q=q.ctypes.data, k_pool=k_pool.ctypes.data, v_pool=v_pool.ctypes.data,
+        block_table=block_table.ctypes.data, row_seq=row_seq.ctypes.data,
+        row_begin=None if row_begin is None else row_begin.ctypes.data, row_end=row_end.ctypes.data,
+        part_o=part_o.ctypes.data, part_lse=part_lse.ctypes.data, n_threads=int(n_threads))
+    st = load_library().omni_host_partial_attn(ctypes.byref(a))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_host_partial_attn")
+    return (part_o, part_lse) if check else st

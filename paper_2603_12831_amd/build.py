@@ -17,6 +17,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libomni_attn.so")
 SOURCES = ["api.hip", "decode_vector.hip", "decode_mfma.hip", "merge.hip", "debug.hip", "kv_cache.hip", "queues.hip"]
+HOST_SOURCES = ["host_attn.cpp"]       # host-only C++ (no device code): compiled with the host compiler
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-pthread", "-Wall", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -44,10 +46,21 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
             raise RuntimeError("hipcc failed on %s" % src)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+    def compile_host(src):
+        obj = os.path.join(out, src.replace(".cpp", ".o"))
+        cxx = os.environ.get("CXX", "g++")
+        r = subprocess.run([cxx, *HOST_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if verbose and (r.stdout or r.stderr):
+            print(r.stdout + r.stderr, file=sys.stderr)
+        if r.returncode != 0:
+            raise RuntimeError("%s failed on %s" % (cxx, src))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + len(HOST_SOURCES))) as ex:
+        host_objs = [ex.submit(compile_host, s) for s in HOST_SOURCES]
+        objs = list(ex.map(compile_one, SOURCES)) + [f.result() for f in host_objs]
     tmp = LIB + ".tmp%d" % os.getpid()
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", tmp, *objs])
     os.replace(tmp, LIB)
     if verbose:
         print("built", LIB)
