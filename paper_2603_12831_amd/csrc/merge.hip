@@ -29,9 +29,9 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     if (row >= (long long)p.batch * p.hq) return;
     const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
 
-    // Rows are visited four at a time so that four independent loads are in flight per lane: the kernel
+    // Rows are visited eight at a time so that eight independent loads are in flight per lane: the kernel
     // is a handful of dependent memory round trips, not a bandwidth problem.
-    constexpr int kBatch = 4;
+    constexpr int kBatch = 8;
     float m = -INFINITY;
     for (int s = 0; s < p.n_srcs; ++s) {
         int r0, r1;
