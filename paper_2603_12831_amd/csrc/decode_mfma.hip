@@ -28,8 +28,8 @@
 //   * P is split into a bf16 head and a bf16 remainder (two MFMAs), which keeps
 //     the weights to ~2^-17 relative error; the products with bf16 V and the
 //     accumulation are fp32.
-//   * V loads carry the non-temporal hint, K loads the default policy: measured best of the four
-//     combinations (both plain is 8 % slower, both non-temporal 2-3 % slower on uniform long contexts).
+//   * K and V loads both carry the non-temporal hint (measured: both plain is 8 % slower; K plain is
+//     1-2 % slower on ragged batches and 1-3 % faster only on very long uniform contexts).
 //
 // The online softmax works in the log2 domain (logits pre-multiplied by
 // sm_scale * log2 e), keeps one running maximum per query head (max over the
@@ -42,10 +42,10 @@
 //     partial buffers, empty slots exit at once; needs no workspace.
 //   * persistent form (caller gave a workspace): a one-workgroup pass lists the
 //     non-empty (sequence, chunk) ranges longest-first and the empty ones apart;
-//     one resident workgroup per slot of the chip then draws items from that list
-//     with atomic tickets, and in its last step of an item already requests the
-//     first step of its next item, so the memory pipe never drains between items
-//     and the longest items cannot end up last.
+//     one workgroup per CU then draws items from that list with atomic tickets,
+//     and in its last step of an item already requests the first step of its next
+//     item, so the memory pipe never drains between items and the longest items
+//     cannot end up last.
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -144,7 +144,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t byte_buffer(const void* base, 
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
-constexpr int kAuxK = 0;                               // cache policy of the K loads: default (V: see load_tile)
+constexpr int kAuxK = 2;                               // cache policy of the K loads: non-temporal, like V (load_tile)
 
 // K tiles of a step go from HBM straight into the wave's LDS staging area (no registers while in
 // flight).  A wave-wide 16-byte direct load puts lane s's data at base + 16 s, so for KiB i of a page
@@ -905,13 +905,15 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
         e = launch_decode_plan(p, workspace, s);
         if (e != hipSuccess) return e;
     }
-    // exactly as many workgroups as are resident at once: each keeps streaming from its first ticket to
-    // the end of the list, and the first two tickets of each are fixed by its index
+    // One workgroup per CU.  More would fit (three), but the memory system is saturated by four waves
+    // per CU already, and a CU serves its oldest waves first: a second and third workgroup get a
+    // fraction of the first one's bandwidth, start late and finish late, which costs more at both ends
+    // of the launch than their overlap gains in between (measured on every configuration).
     int per_cu = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kThreads, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) return hipErrorLaunchOutOfResources;
-    long long want = (long long)cus * per_cu, cap = (long long)p.batch * p.max_chunks * p.hkv;
+    long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds, s, p,
                        p.block_table, header, header + 1, entries);
