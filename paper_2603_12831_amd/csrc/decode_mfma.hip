@@ -610,7 +610,8 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 
 // Work list of a call: the non-empty (sequence, chunk) ranges, longest first, from the front of
 // `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
-// of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here).
+// of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here),
+// word 5 number of waves that ever gave up waiting for a ticket (zeroed here; stays zero).
 // Depends only on the ranges and the chunking, so a list can serve every call that shares them (all
 // layers of one decoding iteration).
 constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
@@ -669,6 +670,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
             header[1] = incl;
             header[2] = hist[kSortBins];
             header[3] = 0;
+            header[5] = 0;
             hist[kSortBins] = 0;
         }
     }
@@ -737,7 +739,8 @@ __device__ __forceinline__ void persistent_body(
     // for thread 0, which never waits for anybody between barriers), reads the item's description and
     // first pages, and in that last step streams the first step of item k+1 instead of a further step
     // of item k, so the memory pipe does not drain between items.
-    constexpr unsigned kPending = 0xffffffffu;
+    constexpr unsigned kPending = 0xffffffffu, kPollLimit = 1u << 24;
+    bool gave_up = false;
     const unsigned first_dynamic = gridDim.x;
     auto short_item = [](const Item& x) { return x.n_steps <= kWaves; };
     unsigned tk = blockIdx.x;
@@ -782,9 +785,15 @@ __device__ __forceinline__ void persistent_body(
 
         // the next item's ticket, description and first pages of this wave
         auto acquire = [&] {
-            unsigned tn;
-            while ((tn = lds_peek(slot_next)) == kPending) __builtin_amdgcn_s_sleep(1);
-            tn = __builtin_amdgcn_readfirstlane(tn);
+            // (the poll is bounded, about a second: should the ticket never come, the wave takes that as
+            // "no further item", which ends the workgroup after this item instead of hanging the GPU)
+            unsigned tn = kPending;
+            for (unsigned n = 0; n < kPollLimit; ++n) {
+                tn = __builtin_amdgcn_readfirstlane(lds_peek(slot_next));
+                if (tn != kPending) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (tn == kPending) gave_up = true;
             has_next = tn < n_tickets;
             if (has_next) {
                 nx = ticket_item(p, entries, block_table, tn);
@@ -832,6 +841,7 @@ __device__ __forceinline__ void persistent_body(
         it = nx;
     }
     OMNI_WAIT_VMCNT(0);                                    // no direct-to-LDS load may outlive the workgroup
+    if (gave_up && id.lane == 0) atomicAdd(ticket_counter + 5, 1u);
 }
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work

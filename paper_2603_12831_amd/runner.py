@@ -42,7 +42,7 @@ class DeviceWorkload:
                 chunk_tokens=c.chunk_tokens, max_chunks=c.max_chunks,
                 part_o=torch.empty((B, c.max_chunks, Hq, D), dtype=torch.float32, device=self.device),
                 part_lse=torch.empty((B, c.max_chunks, Hq), dtype=torch.float32, device=self.device),
-                workspace=torch.empty(binding.omni_decode_workspace_bytes(B, c.max_chunks), dtype=torch.uint8,
+                workspace=torch.zeros(binding.omni_decode_workspace_bytes(B, c.max_chunks), dtype=torch.uint8,
                                       device=self.device) if workspace else None))
         self.ext = None
         if ext_o is not None:
@@ -109,6 +109,11 @@ class DeviceWorkload:
         """One pass of the whole hot path: every decode call, then the merge."""
         self.run_attention(kernel, pool, stream)
         self.run_merge(stream)
+
+    def abandoned_waves(self) -> int:
+        """Diagnostic word of the work lists: waves that gave a launch up (always 0 in a healthy run)."""
+        torch.cuda.synchronize(self.device)
+        return sum(int(c["workspace"][20:24].view(torch.int32).item()) for c in self.calls if c["workspace"] is not None)
 
     def results(self):
         torch.cuda.synchronize(self.device)

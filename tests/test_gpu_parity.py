@@ -87,6 +87,7 @@ def run_and_check(w, kernel, out_dtype="f32", tol=None, ext=None, expected=None)
     dw.poison_outputs()
     dw.run(kernel=kernel[0])
     got_o, got_l = dw.results()
+    assert dw.abandoned_waves() == 0
     exp_o, exp_l = expected if expected is not None else expected_full(w)
     return check(got_o, got_l, exp_o, exp_l, tol or TOL[w.dtype], w.name), dw
 
