@@ -367,12 +367,10 @@ struct Tail {
 // step of this item, `after_last` runs right after it.
 template <bool chained, class Penult, class Before, class After>
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
-                                         const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur,
+                                         const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur, Pages nxt,
                                          Penult&& at_penult, Before&& before_last, After&& after_last)
 {
     int s = id.wave;
-    Pages nxt = {-1, -1};
-    if (s + kWaves < it.n_steps) nxt = step_pages(p, it, s + kWaves);
     // everything older than the first step's 8 K + 8 V requests has landed
     OMNI_WAIT_VMCNT(16);
     while (s + kWaves < it.n_steps) {
@@ -556,12 +554,13 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     WaveState st;
     st.reset();
     StepRegs r;
-    Pages cur = {-1, -1};
+    Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
-    run_item<false>(p, it, st, r, qb, id, scale2, cur, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
+    if (id.wave + kWaves < it.n_steps) second = step_pages(p, it, id.wave + kWaves);
+    run_item<false>(p, it, st, r, qb, id, scale2, cur, second, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
     __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
@@ -759,11 +758,12 @@ __device__ __forceinline__ void persistent_body(
     }
     if (id.wave == 0) issue_q(p, it, id.lane, q_base);
     StepRegs r;
-    Pages cur = {-1, -1};
+    Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
     if (id.wave < it.n_steps) {
         cur = step_pages(p, it, id.wave);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
+    if (id.wave + kWaves < it.n_steps) second = step_pages(p, it, id.wave + kWaves);
     store_empty_share();
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
@@ -779,6 +779,7 @@ __device__ __forceinline__ void persistent_body(
         const bool streamed = id.wave < it.n_steps;
         Item nx = it;
         Tail tail = {false, 0, Pages{-1, -1}};
+        Pages next_second = {-1, -1};
         bool has_next = false;
         unsigned t1 = 0, t2 = 0;
         bool draw2 = false;
@@ -798,10 +799,14 @@ __device__ __forceinline__ void persistent_body(
             if (has_next) {
                 nx = ticket_item(p, entries, block_table, tn);
                 if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
+                // the table reads for the wave's second step of that item go out now as well: at the
+                // item's start they would be a cold round trip in front of its second request
+                next_second = Pages{-1, -1};
+                if (id.wave + kWaves < nx.n_steps) next_second = step_pages(p, nx, id.wave + kWaves);
             }
         };
 
-        run_item<true>(p, it, st, r, qb, id, scale2, cur,
+        run_item<true>(p, it, st, r, qb, id, scale2, cur, second,
                  [&](bool before) {
                      if (threadIdx.x == 0 && late_draw) {
                          if (before) t1 = atomicAdd(ticket_counter, 1u);
@@ -827,6 +832,7 @@ __device__ __forceinline__ void persistent_body(
         // it); then the workgroup meets for the combine with all those loads still in flight
         stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
         cur = tail.pages;
+        second = next_second;
         if (tail.valid && !streamed) {
             issue_step(p, nx.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
         }
