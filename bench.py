@@ -13,6 +13,8 @@ of the partials.  The default workload is the GQA batch-256 decode step
   roofline   the decode-attention kernel alone: algorithmic bytes per launch /
              its mean duration measured with events on the launch stream,
              against the 8 TB/s HBM peak
+  list_kernel_ms, merge_kernel_ms   the other two kernels of a step (mean of 50 back-to-back launches);
+             stream_read_GBps: a plain streaming read of the K pool, pct_of_stream_read: value against it
   cpu_baseline  the CPU fp64 oracle timed on this host on the same workload
 """
 from __future__ import annotations
@@ -158,6 +160,26 @@ def main() -> int:
                      w.dtype == "bf16" and w.head_dim == 128 and args.kernel != 1 else "decode attention",
                      "algorithmic_bytes_per_launch": alg_bytes // len(w.calls)},
     }
+
+    # After the timed loop: the other two kernels of a step, each bracketed by events of its own, and the
+    # read rate of a plain streaming kernel over the same K pool (what this GPU's HBM gives a pure read).
+    def timed(fn, n=50):                # n launches back to back between one pair of events
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    out["list_kernel_ms"] = timed(dw.plan)
+    out["merge_kernel_ms"] = timed(dw.run_merge)
+    pool0 = dw.k_pools[0]
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    nbytes = min(pool0.numel() * pool0.element_size(), 2 << 30)
+    stream_ms = timed(lambda: binding.omni_debug_stream_read(pool0, sink, nbytes), n=10)
+    out["stream_read_GBps"] = nbytes / (stream_ms * 1e-3) / 1e9
+    out["pct_of_stream_read"] = 100.0 * out["value"] / out["stream_read_GBps"]
 
     if host_producer is not None:
         out["host_partial_producer"] = host_producer
