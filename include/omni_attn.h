@@ -121,7 +121,10 @@ typedef struct {
      * need not survive between calls).  With it the kernel runs in its persistent form: non-empty
      * chunks are listed longest-first and drawn by resident workgroups.  NULL selects the plain
      * grid form.  Two calls that may overlap in time (different streams) need distinct
-     * workspaces.  The vector kernel ignores it.                                              */
+     * workspaces.  The vector kernel ignores it.  The 32-bit word at byte 20 of a workspace that
+     * holds a list is a diagnostic: the list build zeroes it and a wave that gives a launch up
+     * (its bounded wait for the next work item ran out, about a second) adds one; it stays zero
+     * in every healthy run, and a non-zero value means rows of that launch are missing.         */
     void*    workspace;
     uint64_t workspace_bytes;
     /* non-zero: the workspace already holds the work list of exactly these ranges and this
