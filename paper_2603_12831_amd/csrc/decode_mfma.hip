@@ -45,7 +45,8 @@
 //     one workgroup per CU then draws items from that list with atomic tickets,
 //     and in its last step of an item already requests the first step of its next
 //     item, so the memory pipe never drains between items and the longest items
-//     cannot end up last.
+//     cannot end up last.  A fifth wave combines the four streaming waves' states
+//     and does all global stores, one item behind them.
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -59,6 +60,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * kWave;
+constexpr int kPersistentThreads = kThreads + kWave;   // persistent form: four streaming waves and a writer wave
 constexpr int kD = 128;
 constexpr int kPageBytes = kBlockSize * kD * 2;        // one (page, kv head) tile of K or of V
 constexpr float kLog2e = 1.4426950408889634f;
@@ -470,8 +472,10 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
-// after a barrier: merge the waves' states with the log-sum-exp rule and write the item's rows
-__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G)
+// after a barrier: merge the waves' states with the log-sum-exp rule and write the item's rows (only seq,
+// chunk and kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn
+__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
+                                                  int tid, int nthreads)
 {
     const float* sh_acc = lds;
     const float* sh_m = lds + kWaves * G * kD;
@@ -479,29 +483,38 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
     const bool final_row = p.out_o != nullptr;                 // only set when max_chunks == 1
     const long long prow0 = ((long long)it.seq * p.max_chunks + it.chunk) * p.hq + (long long)it.kvh * G;
     const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
-    for (int idx = threadIdx.x; idx < G * kD; idx += kThreads) {
-        const int g = idx >> 7, d = idx & (kD - 1);
+    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
+        const int g = idx >> 5, d = (idx & 31) * 4;
         float mm = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
-        float o = 0.f, lse = -INFINITY;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        float lse = -INFINITY;
         if (mm != -INFINITY) {
-            float ll = 0.f, oo = 0.f;
+            float ll = 0.f;
+            f32x4 oo = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
                 const float mw = sh_m[w * 16 + g];
                 const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
                 ll += f * sh_l[w * 16 + g];
-                oo += f * sh_acc[(w * G + g) * kD + d];
+                oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + d);
             }
-            o = oo / ll;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
             lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
-            if (p.part_o) p.part_o[(prow0 + g) * kD + d] = o;
+            if (p.part_o) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
         }
-        if (p.part_lse && d == 0) p.part_lse[prow0 + g] = lse;
+        if (p.part_lse && d == 0) __builtin_nontemporal_store(lse, p.part_lse + prow0 + g);
         if (final_row) {
-            if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[(orow0 + g) * kD + d] = f32_to_bf16(o);
-            else static_cast<float*>(p.out_o)[(orow0 + g) * kD + d] = o;
+            if (p.out_bf16) {
+                uint2 pk;
+                pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+                pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_o) + (orow0 + g) * kD + d) = pk;
+            } else {
+                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out_o) + (orow0 + g) * kD + d) = o;
+            }
             if (p.out_lse && d == 0) p.out_lse[orow0 + g] = lse;
         }
     }
@@ -564,7 +577,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
-    combine_and_store(p, it, lds, p.group);
+    combine_and_store(p, it, lds, p.group, threadIdx.x, kThreads);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -709,7 +722,9 @@ __device__ __forceinline__ void persistent_body(
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ unsigned sh_ticket[3];
-    char* const stage_base = reinterpret_cast<char*>(lds) + combine_bytes(p.group);
+    __shared__ int sh_item[2][4];                          // by item parity: seq, chunk, kvh, 1 if the workgroup's last
+    const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by item parity
+    char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
     char* const q_base = stage_base + kWaves * kStageBytes;          // two buffers of G rows, by item parity
     const int q_bytes = p.group * kD * 2;
     const LaneIds id(stage_base);
@@ -723,7 +738,7 @@ __device__ __forceinline__ void persistent_body(
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
             const WorkEntry w = load_invariant(entries + (last - i));
             store_empty(p, min(max(w.seq, 0), p.batch - 1), min(max(w.chunk, 0), p.max_chunks - 1), 0, p.hq,
-                        threadIdx.x, kThreads);
+                        id.lane, kWave);
         }
     };
 
@@ -743,8 +758,35 @@ __device__ __forceinline__ void persistent_body(
     const unsigned first_dynamic = gridDim.x;
     auto short_item = [](const Item& x) { return x.n_steps <= kWaves; };
     unsigned tk = blockIdx.x;
+    const bool writer = id.wave == kWaves;                 // the fifth wave
     if (tk >= n_tickets) {
+        if (writer) store_empty_share();
+        return;
+    }
+
+    // The writer wave does every global store of the workgroup: the rows of empty chunks now, then, item
+    // after item, the combine of the four streaming waves' states and the item's rows.  A store counts in
+    // the issuing wave's vector-memory counter until the L2 has taken it, and the counter retires in
+    // order, so a store between a streaming wave's loads holds back its waits on younger loads; the
+    // writer has no loads to wait for (measured: 0.5-2 % on batches of short items, nothing on long
+    // ones).  It meets the streaming waves at one barrier per item; the combine areas alternate, so it
+    // combines item k while the others stream item k+1.  The partial rows carry the non-temporal hint:
+    // plain stores of these few bytes (0.5 % of the traffic) cost 3-4 % of the read rate on long
+    // contexts with many chunks, whichever wave issues them.
+    if (writer) {
         store_empty_share();
+        lds_barrier();
+        for (int k = 0;; ++k) {
+            lds_barrier();                                 // item k is staged
+            Item done;
+            done.seq = sh_item[k & 1][0];
+            done.chunk = sh_item[k & 1][1];
+            done.kvh = sh_item[k & 1][2];
+            const bool last = sh_item[k & 1][3] != 0;
+            combine_and_store(p, done, reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes),
+                              p.group, id.lane, kWave);
+            if (last) break;
+        }
         return;
     }
 
@@ -764,7 +806,6 @@ __device__ __forceinline__ void persistent_body(
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
     if (id.wave + kWaves < it.n_steps) second = step_pages(p, it, id.wave + kWaves);
-    store_empty_share();
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
     u32x4 qb[4];
@@ -827,20 +868,26 @@ __device__ __forceinline__ void persistent_body(
                  });
         if (!streamed) acquire();
 
-        // accumulators go to LDS; waves that had no step in this item request their first step of the next
-        // one now; wave 0 makes sure the next Q has landed (it is older than the 16 K/V requests behind
-        // it); then the workgroup meets for the combine with all those loads still in flight
-        stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
+        // accumulators go to LDS (the item's combine area); waves that had no step in this item request
+        // their first step of the next one now; wave 0 makes sure the next Q has landed (it is older than
+        // the 16 K/V requests behind it) and says which item this was; then the workgroup meets, with all
+        // those loads still in flight, and the writer wave takes over the item
+        stage_wave_state(st, reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (k & 1) * comb_bytes), p.group, id.wave,
+                         id.col, id.kg);
         cur = tail.pages;
         second = next_second;
         if (tail.valid && !streamed) {
             issue_step(p, nx.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
         }
         if (id.wave == 0) OMNI_WAIT_VMCNT(16);
+        if (threadIdx.x == 0) {
+            sh_item[k & 1][0] = it.seq;
+            sh_item[k & 1][1] = it.chunk;
+            sh_item[k & 1][2] = it.kvh;
+            sh_item[k & 1][3] = has_next ? 0 : 1;
+        }
         lds_barrier();
-        combine_and_store(p, it, lds, p.group);
         if (!has_next) break;
-        lds_barrier();                                     // LDS is rewritten by the next item's staging
         if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by item k+4
         read_q(q_next, p.group, id.col, id.kg, qb);
         st.reset();
@@ -852,7 +899,7 @@ __device__ __forceinline__ void persistent_body(
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
-__global__ __launch_bounds__(kThreads, 3) void decode_mfma_persistent_kernel(
+__global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
 {
@@ -872,7 +919,7 @@ size_t lds_bytes(int group, bool persistent)
         const size_t a = combine_bytes(group), b = (size_t)kWaves * kStageBytes;
         return a > b ? a : b;
     }
-    return combine_bytes(group) + (size_t)kWaves * kStageBytes + (persistent ? 2 * (size_t)group * kD * 2 : 0);
+    return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)group * kD * 2;
 }
 
 }  // namespace
@@ -926,12 +973,12 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     // fraction of the first one's bandwidth, start late and finish late, which costs more at both ends
     // of the launch than their overlap gains in between (measured on every configuration).
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kThreads, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kPersistentThreads, lds);
     if (e != hipSuccess) return e;
     if (per_cu < 1) return hipErrorLaunchOutOfResources;
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
-    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kThreads), lds, s, p,
+    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p,
                        p.block_table, header, header + 1, entries);
     return hipGetLastError();
 }
