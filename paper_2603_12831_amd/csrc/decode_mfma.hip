@@ -46,7 +46,8 @@
 //     and in its last step of an item already requests the first step of its next
 //     item, so the memory pipe never drains between items and the longest items
 //     cannot end up last.  A fifth wave combines the four streaming waves' states
-//     and does all global stores, one item behind them.
+//     and does all global stores, one item behind them.  Short ranges, when there
+//     are many, are taken four at a time, one whole item per wave.
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -83,6 +84,7 @@ typedef const __attribute__((address_space(1))) void global_void;
 
 struct Item {                // wave-uniform description of a work item
     int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
+    int s0, ds;              // this wave's steps of the item: s0, s0 + ds, ... (ds = 1: the item is this wave's alone)
     const int* __restrict__ table;
 };
 
@@ -216,6 +218,21 @@ __device__ __forceinline__ void finish_item(Item& it, const int* __restrict__ bl
     it.lp_first = it.cb >> 4;
     it.lp_last = (it.ce - 1) >> 4;
     it.n_steps = (it.lp_last - it.lp_first + 2) >> 1;
+}
+
+// Tell the compiler that every field of an item is the same in all lanes (it is: items are derived from
+// wave-uniform tickets), where its own analysis gives up; otherwise the fields move to vector registers
+// and the table reads become vector loads with full waits.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ void make_uniform(Item& it)
+{
+    it.seq = uniform(it.seq); it.chunk = uniform(it.chunk); it.kvh = uniform(it.kvh);
+    it.cb = uniform(it.cb); it.ce = uniform(it.ce);
+    it.lp_first = uniform(it.lp_first); it.lp_last = uniform(it.lp_last); it.n_steps = uniform(it.n_steps);
+    it.s0 = uniform(it.s0); it.ds = uniform(it.ds);
+    const unsigned long long t = reinterpret_cast<unsigned long long>(it.table);
+    const unsigned lo = (unsigned)uniform((int)(unsigned)t), hi = (unsigned)uniform((int)(unsigned)(t >> 32));
+    it.table = reinterpret_cast<const int*>(((unsigned long long)hi << 32) | (unsigned long long)lo);
 }
 
 struct WaveState {
@@ -372,19 +389,19 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
                                          const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur, Pages nxt,
                                          Penult&& at_penult, Before&& before_last, After&& after_last)
 {
-    int s = id.wave;
+    int s = it.s0;
     // everything older than the first step's 8 K + 8 V requests has landed
     OMNI_WAIT_VMCNT(16);
-    while (s + kWaves < it.n_steps) {
-        const bool penult = s + 2 * kWaves >= it.n_steps;
+    while (s + it.ds < it.n_steps) {
+        const bool penult = s + 2 * it.ds >= it.n_steps;
         Pages nn = {-1, -1};
-        if (!penult) nn = step_pages(p, it, s + 2 * kWaves);                       // table reads run a step ahead
+        if (!penult) nn = step_pages(p, it, s + 2 * it.ds);                        // table reads run a step ahead
         else at_penult(true);
         attend_step<true>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2);
         if (penult) at_penult(false);
         cur = nxt;
         nxt = nn;
-        s += kWaves;
+        s += it.ds;
     }
     if (s < it.n_steps) {
         const Tail tail = before_last();
@@ -448,7 +465,8 @@ __device__ __forceinline__ void read_q(const char* qbuf, int group, int col, int
 }
 
 // Dynamic LDS of a workgroup: the cross-wave combine area ([kWaves][G][kD] accumulators, then
-// [kWaves][16] m and l), the waves' K staging areas and, in the persistent form, two Q buffers.
+// [kWaves][16] m and l), the waves' K staging areas and, in the persistent form (which has two combine
+// areas), two sets of per-wave Q buffers.
 __host__ __device__ __forceinline__ size_t combine_bytes(int group)
 {
     return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float);
@@ -472,10 +490,10 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
-// after a barrier: merge the waves' states with the log-sum-exp rule and write the item's rows (only seq,
-// chunk and kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn
+// after a barrier: merge the states of waves w0 .. w1-1 with the log-sum-exp rule and write the item's rows
+// (only seq, chunk and kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn
 __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
-                                                  int tid, int nthreads)
+                                                  int tid, int nthreads, int w0 = 0, int w1 = kWaves)
 {
     const float* sh_acc = lds;
     const float* sh_m = lds + kWaves * G * kD;
@@ -487,14 +505,14 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
         const int g = idx >> 5, d = (idx & 31) * 4;
         float mm = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
+        for (int w = w0; w < w1; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         float lse = -INFINITY;
         if (mm != -INFINITY) {
             float ll = 0.f;
             f32x4 oo = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
+            for (int w = w0; w < w1; ++w) {
                 const float mw = sh_m[w * 16 + g];
                 const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
                 ll += f * sh_l[w * 16 + g];
@@ -561,6 +579,8 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
         return;
     }
     finish_item(it, block_table, p.max_blocks);
+    it.s0 = id.wave;
+    it.ds = kWaves;
     const float scale2 = p.sm_scale * kLog2e;
     u32x4 qb[4];
     load_q(p, it, id.col, id.kg, qb);
@@ -586,12 +606,21 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
 // Workspace: 16 words of header (see decode_list_kernel), then batch * max_chunks entries.
 constexpr int kHeaderWords = 16;
 
+// Ranges of up to kShortTokens tokens ("short") are dealt out one per wave, four to a ticket; the sort keeps
+// them apart from the longer ones: bins 0 .. kLongBins-1 hold the longer ranges by scaled page count (bin 0
+// the longest), then comes one bin per page count of the short ones, so that the first short entry of the
+// sorted list is known exactly.
+constexpr int kShortTokens = 256;
+constexpr int kShortPages = kShortTokens / kBlockSize;
+constexpr int kLongBins = kSortBins - kShortPages;
+
 __device__ __forceinline__ int sort_bin(int tokens, float bins_per_page)
 {
     const int pages = (tokens + kBlockSize - 1) / kBlockSize;
+    if (tokens <= kShortTokens) return kSortBins - pages;
     int b = (int)((float)pages * bins_per_page);
-    if (b > kSortBins - 1) b = kSortBins - 1;
-    return (kSortBins - 1) - b;                            // bin 0 holds the longest ranges
+    if (b > kLongBins - 1) b = kLongBins - 1;
+    return (kLongBins - 1) - b;
 }
 
 // Every active lane takes one slot of counters[key].  The two keys that whole waves tend to share (`hot_a`:
@@ -623,7 +652,8 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 // Work list of a call: the non-empty (sequence, chunk) ranges, longest first, from the front of
 // `entries`; the empty ones from the back.  Header: word 0 ticket counter (zeroed here), word 1 number
 // of non-empty entries, word 2 number of empty ones, word 3 count of departed workgroups (zeroed here),
-// word 5 number of waves that ever gave up waiting for a ticket (zeroed here; stays zero).
+// word 5 number of waves that ever gave up waiting for a ticket (zeroed here; stays zero), word 6 number
+// of non-empty entries longer than kShortTokens (they come first).
 // Depends only on the ranges and the chunking, so a list can serve every call that shares them (all
 // layers of one decoding iteration).
 constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
@@ -635,7 +665,8 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
     __shared__ int sh_b[kListCachedSeqs], sh_e[kListCachedSeqs];
     const int total = p.batch * p.max_chunks;
     const int max_pages = p.chunk_tokens / kBlockSize > 0 ? p.chunk_tokens / kBlockSize : 1;
-    const float bins_per_page = (float)(kSortBins - 1) / (float)max_pages;
+    const float bins_per_page = (float)(kLongBins - 1) / (float)max_pages;
+    const int full_bin = sort_bin(max_pages * kBlockSize, bins_per_page);     // the key whole waves tend to share
     const bool cached = p.batch <= kListCachedSeqs;        // one trip to memory for the ranges, then LDS
     for (int i = threadIdx.x; i < kSortBins + 1; i += blockDim.x) hist[i] = 0;
     if (cached) {
@@ -660,7 +691,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         int seq, chunk, cb = 0, ce = 0;
         if (e < total) entry_range(e, seq, chunk, cb, ce);
         const bool live = ce > cb;
-        wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total, 0, kSortBins);
+        wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total, full_bin, kSortBins);
     }
     __syncthreads();
     if (threadIdx.x < kWave) {                             // exclusive scan by one wave: bin -> first output slot
@@ -676,7 +707,11 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         }
         unsigned run = incl - sum;
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) { hist[threadIdx.x * kPer + i] = run; run += c[i]; }
+        for (int i = 0; i < kPer; ++i) {
+            if (threadIdx.x * kPer + i == kLongBins) header[6] = run;      // entries before the first short one
+            hist[threadIdx.x * kPer + i] = run;
+            run += c[i];
+        }
         if (threadIdx.x == kWave - 1) {
             header[0] = 0;
             header[1] = incl;
@@ -692,18 +727,47 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         int seq = 0, chunk = 0, cb = 0, ce = 0;
         if (e < total) entry_range(e, seq, chunk, cb, ce);
         const bool live = ce > cb;
-        const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total, 0,
-                                             kSortBins);
+        const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total,
+                                             full_bin, kSortBins);
         if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, chunk, cb, ce};
     }
 }
 
-__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
-                                            const int* __restrict__ block_table, unsigned ticket)
+// What the tickets of a launch stand for, in list order (longest ranges first).  Tickets below t_long are
+// one item each: its steps are dealt round-robin to the four streaming waves.  Every further ticket
+// stands for four consecutive items, one per wave: a wave takes all steps of its item, so the workgroup
+// keeps four steps in flight where a short item alone has fewer steps than waves, and one ticket draw
+// serves four items (measured on batches of 32..128-token ranges: 1.3-2.2 x the rate).  Only ranges of up
+// to kShortTokens tokens are grouped, and only if there are enough of them to give every workgroup a
+// grouped ticket: fewer are just the tail of the launch, where the smaller one-item tickets keep the
+// workgroups' finishing times closer together (config 3: grouping its ~800 short ranges costs 1.4 %).
+struct TicketSpace {
+    unsigned n_items, t_long, n_tickets;
+};
+
+__device__ __forceinline__ TicketSpace ticket_space(const DecodeParams& p, const unsigned* __restrict__ counts)
 {
-    const WorkEntry w = load_invariant(entries + ticket / (unsigned)p.hkv);
+    TicketSpace ts;
+    const unsigned n_live = min(counts[0], (unsigned)(p.batch * p.max_chunks));
+    ts.n_items = n_live * (unsigned)p.hkv;
+    ts.t_long = min(counts[5], n_live) * (unsigned)p.hkv;
+    if (ts.n_items - ts.t_long < (unsigned)kWaves * gridDim.x) ts.t_long = ts.n_items;
+    ts.n_tickets = ts.t_long + (ts.n_items - ts.t_long + (unsigned)kWaves - 1u) / (unsigned)kWaves;
+    return ts;
+}
+
+// this wave's item under a ticket (ticket < n_tickets); n_steps = 0 if the wave has none
+__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
+                                            const int* __restrict__ block_table, const TicketSpace& ts,
+                                            unsigned ticket, int wave)
+{
+    const bool grouped = ticket >= ts.t_long;
+    unsigned idx = grouped ? ts.t_long + (unsigned)kWaves * (ticket - ts.t_long) + (unsigned)wave : ticket;
+    const bool valid = idx < ts.n_items;
+    idx = valid ? idx : ts.n_items - 1u;
+    const WorkEntry w = load_invariant(entries + idx / (unsigned)p.hkv);
     Item it;
-    it.kvh = (int)(ticket % (unsigned)p.hkv);
+    it.kvh = (int)(idx % (unsigned)p.hkv);
     // A list that was planned for these very ranges holds only values that pass unchanged; one reused
     // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are the
     // worst that can come of it, never an access outside the table or the output buffers.
@@ -713,8 +777,13 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     it.cb = min(max(w.cb, 0), cap - 1);
     it.ce = min(max(w.ce, it.cb + 1), cap);
     finish_item(it, block_table, p.max_blocks);
+    it.s0 = grouped ? 0 : wave;
+    it.ds = grouped ? 1 : kWaves;
+    if (!valid) it.n_steps = 0;
     return it;
 }
+
+constexpr int kItemWords = 2 + 3 * kWaves;             // what the streaming waves tell the writer about an item
 
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
@@ -722,13 +791,16 @@ __device__ __forceinline__ void persistent_body(
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ unsigned sh_ticket[3];
-    __shared__ int sh_item[2][4];                          // by item parity: seq, chunk, kvh, 1 if the workgroup's last
-    const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by item parity
+    // by ticket parity: [0] 1 if the workgroup's last, [1] 1 if one item per wave, then (seq, chunk, kvh) of
+    // the item (slot 0) or of each wave's item (seq < 0: the wave had none)
+    __shared__ int sh_item[2][kItemWords];
+    const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by ticket parity
     char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
-    char* const q_base = stage_base + kWaves * kStageBytes;          // two buffers of G rows, by item parity
+    char* const q_base = stage_base + kWaves * kStageBytes;          // [parity][wave] buffers of G rows
     const int q_bytes = p.group * kD * 2;
     const LaneIds id(stage_base);
-    const unsigned n_tickets = min(counts[0], (unsigned)(p.batch * p.max_chunks)) * (unsigned)p.hkv;
+    const TicketSpace ts = ticket_space(p, counts);
+    const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
 
     // rows of empty chunks: LSE = -inf (stores only, shared out over the resident workgroups)
@@ -742,21 +814,27 @@ __device__ __forceinline__ void persistent_body(
         }
     };
 
-    // A workgroup's first item is fixed by its index; every further one is drawn from the ticket counter
+    // A workgroup's first ticket is fixed by its index; every further one is drawn from the ticket counter
     // as late as the latencies allow, so that a workgroup that gets little of the memory bandwidth (the
     // CU favours its oldest waves) does not sit on items claimed long ago while the others run dry.
-    // Slot j % 3 of sh_ticket holds the ticket of the workgroup's j-th item once thread 0 knows it
-    // (kPending before).  The ticket of item k+1 is drawn by thread 0 before its second-to-last step of
-    // item k and published after that step; if item k is too short for that (a single step per wave) it
-    // is drawn a whole item earlier, in the last step of item k-1 (for k = 0: at the start).  Every wave
-    // picks the ticket up right before its own last step of item k (waiting, if it got there first,
-    // for thread 0, which never waits for anybody between barriers), reads the item's description and
-    // first pages, and in that last step streams the first step of item k+1 instead of a further step
-    // of item k, so the memory pipe does not drain between items.
+    // Slot j % 3 of sh_ticket holds the workgroup's j-th ticket once thread 0 knows it (kPending before).
+    // Ticket k+1 is drawn by thread 0 before its second-to-last step of ticket k and published after that
+    // step; if its wave has fewer than two steps under ticket k, it is drawn a whole ticket earlier, in the
+    // last step of ticket k-1 (for k = 0: at the start).  Every wave picks the ticket up right before its
+    // own last step of ticket k (waiting, if it got there first, for thread 0, which never waits for
+    // anybody between barriers), reads its item's description and first pages, and in that last step
+    // streams the first step of its next item instead of a further step of this one, so the memory pipe
+    // does not drain between items.
     constexpr unsigned kPending = 0xffffffffu, kPollLimit = 1u << 24;
     bool gave_up = false;
     const unsigned first_dynamic = gridDim.x;
-    auto short_item = [](const Item& x) { return x.n_steps <= kWaves; };
+    auto short_item = [](const Item& x) { return x.n_steps <= x.s0 + x.ds; };      // fewer than two steps for this wave
+    auto has_steps = [](const Item& x) { return x.s0 < x.n_steps; };
+    // who brings an item's Q rows into LDS, and where: wave 0 for all, or every wave for its own item
+    auto brings_q = [&](const Item& x) { return x.ds == 1 ? x.n_steps > 0 : id.wave == 0; };
+    auto q_buffer = [&](int parity, const Item& x) {
+        return q_base + (parity * kWaves + (x.ds == 1 ? id.wave : 0)) * q_bytes;
+    };
     unsigned tk = blockIdx.x;
     const bool writer = id.wave == kWaves;                 // the fifth wave
     if (tk >= n_tickets) {
@@ -764,71 +842,82 @@ __device__ __forceinline__ void persistent_body(
         return;
     }
 
-    // The writer wave does every global store of the workgroup: the rows of empty chunks now, then, item
-    // after item, the combine of the four streaming waves' states and the item's rows.  A store counts in
-    // the issuing wave's vector-memory counter until the L2 has taken it, and the counter retires in
-    // order, so a store between a streaming wave's loads holds back its waits on younger loads; the
-    // writer has no loads to wait for (measured: 0.5-2 % on batches of short items, nothing on long
-    // ones).  It meets the streaming waves at one barrier per item; the combine areas alternate, so it
-    // combines item k while the others stream item k+1.  The partial rows carry the non-temporal hint:
-    // plain stores of these few bytes (0.5 % of the traffic) cost 3-4 % of the read rate on long
-    // contexts with many chunks, whichever wave issues them.
+    // The writer wave does every global store of the workgroup: the rows of empty chunks now, then, ticket
+    // after ticket, the combine of the four streaming waves' states and the rows of the item (or of the
+    // waves' four items, which need no combine).  A store counts in the issuing wave's vector-memory
+    // counter until the L2 has taken it, and the counter retires in order, so a store between a streaming
+    // wave's loads holds back its waits on younger loads; the writer has no loads to wait for (measured:
+    // 0.5-2 % on batches of short items, nothing on long ones).  It meets the streaming waves at one
+    // barrier per ticket; the combine areas alternate, so it works on ticket k while the others stream
+    // ticket k+1.  The partial rows carry the non-temporal hint: plain stores of these few bytes (0.5 % of
+    // the traffic) cost 3-4 % of the read rate on long contexts with many chunks, whichever wave issues them.
     if (writer) {
         store_empty_share();
         lds_barrier();
         for (int k = 0;; ++k) {
-            lds_barrier();                                 // item k is staged
+            lds_barrier();                                 // ticket k is staged
+            const int* si = sh_item[k & 1];
+            const bool last = si[0] != 0, grouped = si[1] != 0;
+            const float* area = reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes);
             Item done;
-            done.seq = sh_item[k & 1][0];
-            done.chunk = sh_item[k & 1][1];
-            done.kvh = sh_item[k & 1][2];
-            const bool last = sh_item[k & 1][3] != 0;
-            combine_and_store(p, done, reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes),
-                              p.group, id.lane, kWave);
+            if (!grouped) {
+                done.seq = si[2];
+                done.chunk = si[3];
+                done.kvh = si[4];
+                combine_and_store(p, done, area, p.group, id.lane, kWave);
+            } else {
+                for (int w = 0; w < kWaves; ++w) {
+                    done.seq = si[2 + 3 * w];
+                    done.chunk = si[3 + 3 * w];
+                    done.kvh = si[4 + 3 * w];
+                    if (done.seq >= 0) combine_and_store(p, done, area, p.group, id.lane, kWave, w, w + 1);
+                }
+            }
             if (last) break;
         }
         return;
     }
 
-    // first item: wave 0 brings Q into LDS, every wave requests its first step, then all read Q; the
-    // stores for the empty rows go out while those first loads are on their way
-    Item it = ticket_item(p, entries, block_table, tk);
+    // first ticket: Q goes into LDS, every wave requests its first step, then all read Q; the stores for
+    // the empty rows go out while those first loads are on their way
+    Item it = ticket_item(p, entries, block_table, ts, tk, id.wave);
     if (threadIdx.x == 0) {
         sh_ticket[0] = kPending;
         sh_ticket[2] = kPending;
         sh_ticket[1] = short_item(it) ? first_dynamic + atomicAdd(ticket_counter, 1u) : kPending;
     }
-    if (id.wave == 0) issue_q(p, it, id.lane, q_base);
+    if (brings_q(it)) issue_q(p, it, id.lane, q_buffer(0, it));
     StepRegs r;
     Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
-    if (id.wave < it.n_steps) {
-        cur = step_pages(p, it, id.wave);
+    if (has_steps(it)) {
+        cur = step_pages(p, it, it.s0);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
-    if (id.wave + kWaves < it.n_steps) second = step_pages(p, it, id.wave + kWaves);
+    if (it.s0 + it.ds < it.n_steps) second = step_pages(p, it, it.s0 + it.ds);
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
     u32x4 qb[4];
-    read_q(q_base, p.group, id.col, id.kg, qb);
+    read_q(q_buffer(0, it), p.group, id.col, id.kg, qb);
     WaveState st;
     st.reset();
 
     for (int k = 0;; ++k) {
+        make_uniform(it);                                  // (the loop-carried copy is where the analysis gives up)
         unsigned* const slot_next = &sh_ticket[(k + 1) % 3];
-        char* const q_next = q_base + ((k + 1) & 1) * q_bytes;
+        const int parity_next = (k + 1) & 1;
         const bool late_draw = !short_item(it);
-        const bool streamed = id.wave < it.n_steps;
+        const bool streamed = has_steps(it);
         Item nx = it;
         Tail tail = {false, 0, Pages{-1, -1}};
         Pages next_second = {-1, -1};
-        bool has_next = false;
+        bool has_next = false, q_coming = false;
         unsigned t1 = 0, t2 = 0;
         bool draw2 = false;
 
-        // the next item's ticket, description and first pages of this wave
+        // the next ticket, this wave's item under it and the item's first pages
         auto acquire = [&] {
             // (the poll is bounded, about a second: should the ticket never come, the wave takes that as
-            // "no further item", which ends the workgroup after this item instead of hanging the GPU)
+            // "no further ticket", which ends the workgroup after this one instead of hanging the GPU)
             unsigned tn = kPending;
             for (unsigned n = 0; n < kPollLimit; ++n) {
                 tn = __builtin_amdgcn_readfirstlane(lds_peek(slot_next));
@@ -838,12 +927,15 @@ __device__ __forceinline__ void persistent_body(
             if (tn == kPending) gave_up = true;
             has_next = tn < n_tickets;
             if (has_next) {
-                nx = ticket_item(p, entries, block_table, tn);
-                if (id.wave < nx.n_steps) tail = Tail{true, nx.kvh, step_pages(p, nx, id.wave)};
+                nx = ticket_item(p, entries, block_table, ts, tn, id.wave);
+                if (has_steps(nx)) tail = Tail{true, nx.kvh, step_pages(p, nx, nx.s0)};
                 // the table reads for the wave's second step of that item go out now as well: at the
                 // item's start they would be a cold round trip in front of its second request
                 next_second = Pages{-1, -1};
-                if (id.wave + kWaves < nx.n_steps) next_second = step_pages(p, nx, id.wave + kWaves);
+                if (nx.s0 + nx.ds < nx.n_steps) next_second = step_pages(p, nx, nx.s0 + nx.ds);
+                q_coming = brings_q(nx);
+            } else {
+                nx.n_steps = 0;
             }
         };
 
@@ -856,9 +948,9 @@ __device__ __forceinline__ void persistent_body(
                  },
                  [&] {
                      acquire();
-                     // wave 0 requests the next item's Q into the other Q buffer; a short next item has
-                     // no second-to-last step to draw its successor's ticket in: thread 0 draws it now
-                     if (has_next && id.wave == 0) issue_q(p, nx, id.lane, q_next);
+                     // the next Q goes into the other set of Q buffers; if thread 0's wave has no
+                     // second-to-last step under the next ticket to draw its successor in, it draws it now
+                     if (q_coming) issue_q(p, nx, id.lane, q_buffer(parity_next, nx));
                      draw2 = has_next && short_item(nx);
                      if (threadIdx.x == 0 && draw2) t2 = atomicAdd(ticket_counter, 1u);
                      return tail;
@@ -866,30 +958,39 @@ __device__ __forceinline__ void persistent_body(
                  [&] {
                      if (threadIdx.x == 0 && draw2) lds_post(&sh_ticket[(k + 2) % 3], first_dynamic + t2);
                  });
-        if (!streamed) acquire();
+        // waves that had no step under this ticket request their Q and first step of the next one now
+        if (!streamed) {
+            acquire();
+            if (q_coming) issue_q(p, nx, id.lane, q_buffer(parity_next, nx));
+        }
 
-        // accumulators go to LDS (the item's combine area); waves that had no step in this item request
-        // their first step of the next one now; wave 0 makes sure the next Q has landed (it is older than
-        // the 16 K/V requests behind it) and says which item this was; then the workgroup meets, with all
-        // those loads still in flight, and the writer wave takes over the item
-        stage_wave_state(st, reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (k & 1) * comb_bytes), p.group, id.wave,
-                         id.col, id.kg);
+        // accumulators go to LDS (the ticket's combine area); whoever requested Q rows makes sure they have
+        // landed (they are older than the 16 K/V requests behind them); the waves say which items these
+        // were; then the workgroup meets, with all those loads still in flight, and the writer wave takes
+        // over
+        float* const area = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (k & 1) * comb_bytes);
+        stage_wave_state(st, area, p.group, id.wave, id.col, id.kg);
         cur = tail.pages;
         second = next_second;
         if (tail.valid && !streamed) {
             issue_step(p, nx.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
         }
-        if (id.wave == 0) OMNI_WAIT_VMCNT(16);
-        if (threadIdx.x == 0) {
-            sh_item[k & 1][0] = it.seq;
-            sh_item[k & 1][1] = it.chunk;
-            sh_item[k & 1][2] = it.kvh;
-            sh_item[k & 1][3] = has_next ? 0 : 1;
+        if (q_coming) OMNI_WAIT_VMCNT(16);
+        const bool grouped = it.ds == 1;
+        if (id.lane == 0 && (grouped || id.wave == 0)) {
+            int* si = sh_item[k & 1];
+            if (id.wave == 0) {
+                si[0] = has_next ? 0 : 1;
+                si[1] = grouped ? 1 : 0;
+            }
+            si[2 + 3 * id.wave] = streamed ? it.seq : -1;
+            si[3 + 3 * id.wave] = it.chunk;
+            si[4 + 3 * id.wave] = it.kvh;
         }
         lds_barrier();
         if (!has_next) break;
-        if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by item k+4
-        read_q(q_next, p.group, id.col, id.kg, qb);
+        if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by ticket k+4
+        read_q(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
         st.reset();
         it = nx;
     }
@@ -919,7 +1020,7 @@ size_t lds_bytes(int group, bool persistent)
         const size_t a = combine_bytes(group), b = (size_t)kWaves * kStageBytes;
         return a > b ? a : b;
     }
-    return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)group * kD * 2;
+    return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)kWaves * group * kD * 2;
 }
 
 }  // namespace

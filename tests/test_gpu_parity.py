@@ -356,6 +356,28 @@ def test_ticket_handover_across_item_lengths():
     run_and_check(w, BENCH_FORM, expected=exp)
 
 
+@pytest.mark.parametrize("shape", [(6, 3, 401), (16, 1, 1100), (5, 5, 230), (32, 2, 600)])
+def test_short_ranges_four_to_a_ticket(shape):
+    """Enough ranges of up to 256 tokens for every workgroup to get a ticket of four of them (one per wave),
+    behind a few longer ones that are still one item per ticket: item counts that leave the last ticket
+    partly filled, kv-head counts that make a ticket straddle ranges of different lengths, waves with
+    one to nine steps under one ticket, group sizes 1 to 16; final rows written directly (bf16 and fp32)
+    and partial rows merged."""
+    hq, hkv, batch = shape
+    rng = np.random.default_rng([64, hq, hkv])
+    lengths = rng.integers(1, 257, size=batch)
+    lengths[rng.integers(0, batch, size=7)] = rng.integers(257, 700, size=7)
+    begin = rng.integers(0, 2, size=batch) * rng.integers(0, 40, size=batch)
+    w = wl.make_generic(64 + hq, lengths + begin, hq, hkv, 128, dtype="bf16", ctx_begin=begin)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    # rows stored as bf16 carry that format's rounding (half an ulp: 2^-9 relative) on top of the bound
+    run_and_check(w, BENCH_FORM, expected=exp, out_dtype="bf16",
+                  tol=TOL["bf16"] + float(np.max(np.abs(exp[0]))) * 2.0 ** -9)
+    run_and_check(w, BENCH_FORM, expected=exp, out_dtype="f32")
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 128, 6
+    run_and_check(w, BENCH_FORM, expected=exp)
+
+
 def test_workspace_too_small_is_rejected():
     w = wl.make_generic(63, [100, 50], 8, 2, 128, dtype="bf16", chunk_tokens=32)
     dw = DeviceWorkload(w, out_dtype="f32")
