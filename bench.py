@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per decode-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor the same counters show for the plain copy kernel; None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg3-gqa-b256": 1996.8e6}      # profiles/decode_mfma_persistent_cfg3_pmc.md
+MEASURED_TRAFFIC_BYTES = {"cfg3-gqa-b256": 1997.0e6}      # profiles/decode_mfma_persistent_cfg3_pmc.md
 
 
 def algorithmic_bytes(w) -> int:
