@@ -472,6 +472,13 @@ __host__ __device__ __forceinline__ size_t combine_bytes(int group)
     return (size_t)(kWaves * group * kD + 2 * kWaves * 16) * sizeof(float);
 }
 
+// Position of dim d (a multiple of 4) of head row g inside that row of the combine area.  A lane holds,
+// for each i, eight consecutive dims 32 kg + 8 i .. + 7 of head `col`; rows are 128 floats apart, so
+// without a swizzle the 16 lanes of a 16-byte store (4 heads x 4 k groups, more heads for larger G) would
+// all start in the same bank.  XOR-ing bits 3-4 with the head and bit 2 with the upper k-group bit
+// spreads them over all banks and keeps groups of four dims together for the 16-byte reads of the combine.
+__device__ __forceinline__ int combine_slot(int g, int d) { return d ^ ((g & 3) << 3) ^ ((d >> 6 & 1) << 2); }
+
 __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds, int G, int wave, int col, int kg)
 {
     float l = st.l_run;
@@ -483,9 +490,12 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     if (col < G) {
         float* dst = sh_acc + (wave * G + col) * kD;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dst[(4 * kg + i) * 8 + j] = st.acc[j][i];
+            for (int h = 0; h < 2; ++h) {
+                const f32x4 v = {st.acc[4 * h][i], st.acc[4 * h + 1][i], st.acc[4 * h + 2][i], st.acc[4 * h + 3][i]};
+                *reinterpret_cast<f32x4*>(dst + combine_slot(col, (4 * kg + i) * 8 + 4 * h)) = v;
+            }
         if (kg == 0) { sh_m[wave * 16 + col] = st.m_run; sh_l[wave * 16 + col] = l; }
     }
 }
@@ -516,7 +526,7 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
                 const float mw = sh_m[w * 16 + g];
                 const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
                 ll += f * sh_l[w * 16 + g];
-                oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + d);
+                oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + combine_slot(g, d));
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
