@@ -13,8 +13,7 @@ of the partials.  The default workload is the GQA batch-256 decode step
   roofline   the decode-attention kernel alone: algorithmic bytes per launch /
              its mean duration measured with events on the launch stream,
              against the 8 TB/s HBM peak
-  list_kernel_ms, merge_kernel_ms   the other two kernels of a step (mean of 50 back-to-back launches);
-             stream_read_GBps: a plain streaming read of the K pool, pct_of_stream_read: value against it
+  stream_read_GBps   a plain streaming read of the K pool on the same GPU; pct_of_stream_read: value against it
   cpu_baseline  the CPU fp64 oracle timed on this host on the same workload
 """
 from __future__ import annotations
@@ -161,8 +160,8 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg_bytes // len(w.calls)},
     }
 
-    # After the timed loop: the other two kernels of a step, each bracketed by events of its own, and the
-    # read rate of a plain streaming kernel over the same K pool (what this GPU's HBM gives a pure read).
+    # After the timed loop: the read rate of a plain streaming kernel over the same K pool (what this GPU's
+    # HBM gives a pure read).
     def timed(fn, n=50):                # n launches back to back between one pair of events
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         fn()
@@ -172,8 +171,6 @@ def main() -> int:
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
-    out["list_kernel_ms"] = timed(dw.plan)
-    out["merge_kernel_ms"] = timed(dw.run_merge)
     pool0 = dw.k_pools[0]
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     nbytes = min(pool0.numel() * pool0.element_size(), 2 << 30)
