@@ -14,6 +14,7 @@ of the partials.  The default workload is the GQA batch-256 decode step
              its mean duration measured with events on the launch stream,
              against the 8 TB/s HBM peak
   stream_read_GBps   a plain streaming read of the K pool on the same GPU; pct_of_stream_read: value against it
+  list_reused   the same step when one work list serves many calls (the layers of a decoding iteration)
   cpu_baseline  the CPU fp64 oracle timed on this host on the same workload
 """
 from __future__ import annotations
@@ -171,6 +172,22 @@ def main() -> int:
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
+    # The same step with the work list built once and reused (omni_decode_plan + workspace_planned), as the
+    # layers of one decoding iteration would share it: extra information, never `value`.
+    def step_planned(i):
+        dw.run_attention(kernel=args.kernel, pool=i % args.pools, planned=True)
+        dw.run_merge()
+    dw.plan()
+    for i in range(min(args.warmup, 5)):
+        step_planned(i)
+    torch.cuda.synchronize()
+    p0 = time.perf_counter()
+    for i in range(args.steps):
+        step_planned(i)
+    torch.cuda.synchronize()
+    planned_ms = (time.perf_counter() - p0) * 1e3 / args.steps
+    out["list_reused"] = {"ms_per_step": planned_ms, "value": kv_bytes / (planned_ms * 1e-3) / 1e9, "unit": "GB/s",
+                          "pct_hbm_peak": 100.0 * kv_bytes / (planned_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     pool0 = dw.k_pools[0]
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     nbytes = min(pool0.numel() * pool0.element_size(), 2 << 30)
