@@ -378,6 +378,40 @@ def test_short_ranges_four_to_a_ticket(shape):
     run_and_check(w, BENCH_FORM, expected=exp)
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_seeded_random_batches(case):
+    """Seeded random batches through the form bench.py times: kv-head counts 1-8, group sizes 1-16, batches
+    of many short ranges, few long ones and mixtures, ranges that start past token 0, unchunked and chunked
+    (64 .. 1024 tokens, sometimes with a spare chunk slot); every batch is run twice on its buffers."""
+    rng = np.random.default_rng([65, case])
+    hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    hq = hkv * int(rng.choice([1, 2, 4, 5, 8, 16]))
+    kind = case % 4
+    if kind == 0:
+        lengths = rng.integers(1, 300, size=int(rng.integers(300, 1500)))
+    elif kind == 1:
+        lengths = rng.integers(1, 2500, size=int(rng.integers(50, 400)))
+    elif kind == 2:
+        n = int(rng.integers(200, 900))
+        lengths = np.where(rng.random(n) < 0.1, rng.integers(300, 3000, size=n), rng.integers(1, 260, size=n))
+    else:
+        lengths = rng.integers(1, 6000, size=int(rng.integers(1, 40)))
+    lengths = lengths[:max(1, 40000 // hq)]                  # keeps the oracle quick
+    begin = (rng.random(len(lengths)) < 0.3) * rng.integers(0, 50, size=len(lengths))
+    w = wl.make_generic(6500 + case, lengths + begin, hq, hkv, 128, dtype="bf16", ctx_begin=begin)
+    chunk = int(rng.choice([0, 64, 128, 256, 512, 1024]))
+    if chunk:
+        longest = int((lengths + begin).max())
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, (longest + chunk - 1) // chunk + int(rng.integers(0, 2))
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    (_, _), dw = run_and_check(w, BENCH_FORM, expected=exp)
+    dw.poison_outputs()
+    dw.run(kernel=BENCH_FORM[0])
+    got_o, got_l = dw.results()
+    check(got_o, got_l, exp[0], exp[1], TOL["bf16"], "second pass")
+    assert dw.abandoned_waves() == 0
+
+
 def test_workspace_too_small_is_rejected():
     w = wl.make_generic(63, [100, 50], 8, 2, 128, dtype="bf16", chunk_tokens=32)
     dw = DeviceWorkload(w, out_dtype="f32")
