@@ -412,6 +412,35 @@ def test_seeded_random_batches(case):
     assert dw.abandoned_waves() == 0
 
 
+def test_step_captured_in_a_graph_replays_exactly():
+    """One whole step (work list, decode attention, merge) recorded into a graph on a side stream and
+    replayed several times, with other work of the library and synchronisations in between: every replay
+    must reproduce the directly launched step bit for bit (the work list's counters are put back by the
+    kernel itself, nothing is allocated or cleared by the host between calls)."""
+    w = wl.make_cfg3(batch=40, median=600, lo=1, hi=4000, chunk_tokens=512)
+    exp = expected_full(w)
+    (_, _), dw = run_and_check(w, BENCH_FORM, expected=exp)
+    eager_o, eager_l = dw.results()
+    other = DeviceWorkload(wl.make_generic(66, [300, 17, 1200], 8, 2, 128, dtype="bf16", chunk_tokens=256), out_dtype="f32")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dw.run(kernel=BENCH_FORM[0])                           # warm-up on the capturing stream
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dw.run(kernel=BENCH_FORM[0])
+    for replay in range(4):
+        dw.poison_outputs()
+        other.run(kernel=BENCH_FORM[0])                        # unrelated launches between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got_o, got_l = dw.results()
+        assert np.array_equal(got_o, eager_o) and np.array_equal(got_l, eager_l), "replay %d differs" % replay
+        assert dw.abandoned_waves() == 0
+    check(got_o, got_l, exp[0], exp[1], TOL["bf16"], "graph replay")
+
+
 def test_workspace_too_small_is_rejected():
     w = wl.make_generic(63, [100, 50], 8, 2, 128, dtype="bf16", chunk_tokens=32)
     dw = DeviceWorkload(w, out_dtype="f32")
