@@ -319,6 +319,21 @@ omni_status omni_debug_gather_kv(const omni_decode_args* a, int32_t seq, void* k
 omni_status omni_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/*
+ * Test aids for the persistent form's work list (host only, no GPU call; they run the functions the kernels
+ * use).  omni_debug_sort_bin: the sort key (0 .. 255, smaller = earlier in the list) of a non-empty range of
+ * `tokens` tokens in a call with `chunk_tokens` (0 = unchunked); 256 for tokens <= 0.
+ * omni_debug_ticket_map: for a list of n_entries non-empty ranges whose first n_long_entries are longer
+ * than 256 tokens, num_kv_heads items per entry and n_workgroups workgroups, writes for every ticket t and
+ * streaming wave w (0..3) the pair items[(4 t + w) * 2 + 0] = list item (entry * num_kv_heads + kv head,
+ * -1 = none) and [.. + 1] = 1 if the ticket stands for one item per wave, 0 if all waves share the item;
+ * *n_tickets receives the number of tickets.  Pairs beyond `capacity` ints are not written.
+ * Errors: NULL, SHAPE (num_kv_heads < 1, n_workgroups < 1, more than 2^31 - 1 items).
+ */
+int32_t omni_debug_sort_bin(int32_t tokens, int32_t chunk_tokens);
+omni_status omni_debug_ticket_map(uint32_t n_entries, uint32_t n_long_entries, int32_t num_kv_heads,
+                                  uint32_t n_workgroups, int32_t* items, uint64_t capacity, uint32_t* n_tickets);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
            "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
-           "omni_host_partial_attn")
+           "omni_host_partial_attn", "omni_debug_sort_bin", "omni_debug_ticket_map")
 
 
 class OmniError(RuntimeError):
@@ -107,6 +107,11 @@ def load_library() -> ctypes.CDLL:
         lib.omni_debug_stream_read.restype = ctypes.c_int
         lib.omni_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.omni_debug_copy.restype = ctypes.c_int
+        lib.omni_debug_sort_bin.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.omni_debug_sort_bin.restype = ctypes.c_int32
+        lib.omni_debug_ticket_map.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_uint32, vp,
+                                              ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32)]
+        lib.omni_debug_ticket_map.restype = ctypes.c_int
         qp = ctypes.POINTER(omni_queue)
         lib.omni_queue_push.argtypes = [qp, vp, vp, ctypes.c_int32, vp, vp]
         lib.omni_queue_push.restype = ctypes.c_int
@@ -430,3 +435,21 @@ def omni_host_partial_attn(q, k_pool, v_pool, block_table, row_seq, row_begin, r
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_host_partial_attn")
     return (part_o, part_lse) if check else st
+
+
+def omni_debug_sort_bin(tokens: int, chunk_tokens: int) -> int:
+    return int(load_library().omni_debug_sort_bin(int(tokens), int(chunk_tokens)))
+
+
+def omni_debug_ticket_map(n_entries: int, n_long_entries: int, num_kv_heads: int, n_workgroups: int):
+    """(items [n_tickets, 4] int32 with -1 = none, grouped [n_tickets] bool) of the persistent form's tickets."""
+    import numpy as np
+    cap = (n_entries * max(num_kv_heads, 1) + 4) * 8 + 8
+    buf = np.full(cap, -7, dtype=np.int32)
+    n = ctypes.c_uint32(0)
+    st = load_library().omni_debug_ticket_map(n_entries, n_long_entries, num_kv_heads, n_workgroups,
+                                              buf.ctypes.data_as(ctypes.c_void_p), cap, ctypes.byref(n))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_debug_ticket_map")
+    pairs = buf[:n.value * 8].reshape(n.value, 4, 2)
+    return pairs[:, :, 0].copy(), pairs[:, 0, 1].astype(bool)

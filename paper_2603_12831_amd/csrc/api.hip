@@ -259,4 +259,20 @@ omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
 
+int32_t omni_debug_sort_bin(int32_t tokens, int32_t chunk_tokens)
+{
+    return omni::decode_list_sort_bin(tokens, chunk_tokens);
+}
+
+omni_status omni_debug_ticket_map(uint32_t n_entries, uint32_t n_long_entries, int32_t num_kv_heads,
+                                  uint32_t n_workgroups, int32_t* items, uint64_t capacity, uint32_t* n_tickets)
+{
+    if (!items || !n_tickets) return OMNI_ERR_NULL;
+    if (num_kv_heads < 1 || n_workgroups < 1 || (uint64_t)n_entries * (uint64_t)num_kv_heads > 0x7fffffffull)
+        return OMNI_ERR_SHAPE;
+    *n_tickets = omni::decode_ticket_map(n_entries, n_long_entries, (unsigned)num_kv_heads, n_workgroups, items,
+                                         (size_t)capacity);
+    return OMNI_OK;
+}
+
 }  // extern "C"

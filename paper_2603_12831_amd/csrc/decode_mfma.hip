@@ -624,7 +624,13 @@ constexpr int kShortTokens = 256;
 constexpr int kShortPages = kShortTokens / kBlockSize;
 constexpr int kLongBins = kSortBins - kShortPages;
 
-__device__ __forceinline__ int sort_bin(int tokens, float bins_per_page)
+__host__ __device__ __forceinline__ float sort_bins_per_page(int chunk_tokens)
+{
+    const int max_pages = chunk_tokens / kBlockSize > 0 ? chunk_tokens / kBlockSize : 1;
+    return (float)(kLongBins - 1) / (float)max_pages;
+}
+
+__host__ __device__ __forceinline__ int sort_bin(int tokens, float bins_per_page)
 {
     const int pages = (tokens + kBlockSize - 1) / kBlockSize;
     if (tokens <= kShortTokens) return kSortBins - pages;
@@ -675,7 +681,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
     __shared__ int sh_b[kListCachedSeqs], sh_e[kListCachedSeqs];
     const int total = p.batch * p.max_chunks;
     const int max_pages = p.chunk_tokens / kBlockSize > 0 ? p.chunk_tokens / kBlockSize : 1;
-    const float bins_per_page = (float)(kLongBins - 1) / (float)max_pages;
+    const float bins_per_page = sort_bins_per_page(p.chunk_tokens);
     const int full_bin = sort_bin(max_pages * kBlockSize, bins_per_page);     // the key whole waves tend to share
     const bool cached = p.batch <= kListCachedSeqs;        // one trip to memory for the ranges, then LDS
     for (int i = threadIdx.x; i < kSortBins + 1; i += blockDim.x) hist[i] = 0;
@@ -755,15 +761,31 @@ struct TicketSpace {
     unsigned n_items, t_long, n_tickets;
 };
 
-__device__ __forceinline__ TicketSpace ticket_space(const DecodeParams& p, const unsigned* __restrict__ counts)
+// n_live non-empty list entries, the first n_long of them longer than kShortTokens, hkv items per entry,
+// n_workgroups workgroups in the launch
+__host__ __device__ __forceinline__ TicketSpace make_ticket_space(unsigned n_live, unsigned n_long, unsigned hkv,
+                                                                  unsigned n_workgroups)
 {
     TicketSpace ts;
-    const unsigned n_live = min(counts[0], (unsigned)(p.batch * p.max_chunks));
-    ts.n_items = n_live * (unsigned)p.hkv;
-    ts.t_long = min(counts[5], n_live) * (unsigned)p.hkv;
-    if (ts.n_items - ts.t_long < (unsigned)kWaves * gridDim.x) ts.t_long = ts.n_items;
+    ts.n_items = n_live * hkv;
+    ts.t_long = (n_long < n_live ? n_long : n_live) * hkv;
+    if (ts.n_items - ts.t_long < (unsigned)kWaves * n_workgroups) ts.t_long = ts.n_items;
     ts.n_tickets = ts.t_long + (ts.n_items - ts.t_long + (unsigned)kWaves - 1u) / (unsigned)kWaves;
     return ts;
+}
+
+// list item (entry index * hkv + kv head) of wave `wave` under `ticket`; false if the wave has none
+__host__ __device__ __forceinline__ bool ticket_index(const TicketSpace& ts, unsigned ticket, int wave, unsigned& idx,
+                                                      bool& grouped)
+{
+    grouped = ticket >= ts.t_long;
+    idx = grouped ? ts.t_long + (unsigned)kWaves * (ticket - ts.t_long) + (unsigned)wave : ticket;
+    return idx < ts.n_items;
+}
+
+__device__ __forceinline__ TicketSpace ticket_space(const DecodeParams& p, const unsigned* __restrict__ counts)
+{
+    return make_ticket_space(min(counts[0], (unsigned)(p.batch * p.max_chunks)), counts[5], (unsigned)p.hkv, gridDim.x);
 }
 
 // this wave's item under a ticket (ticket < n_tickets); n_steps = 0 if the wave has none
@@ -771,9 +793,9 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
                                             const int* __restrict__ block_table, const TicketSpace& ts,
                                             unsigned ticket, int wave)
 {
-    const bool grouped = ticket >= ts.t_long;
-    unsigned idx = grouped ? ts.t_long + (unsigned)kWaves * (ticket - ts.t_long) + (unsigned)wave : ticket;
-    const bool valid = idx < ts.n_items;
+    bool grouped;
+    unsigned idx;
+    const bool valid = ticket_index(ts, ticket, wave, idx, grouped);
     idx = valid ? idx : ts.n_items - 1u;
     const WorkEntry w = load_invariant(entries + idx / (unsigned)p.hkv);
     Item it;
@@ -1044,6 +1066,28 @@ bool decode_mfma_supports(const DecodeParams& p, bool bf16)
 size_t decode_workspace_bytes(long long batch, long long max_chunks)
 {
     return (size_t)kHeaderWords * sizeof(unsigned) + (size_t)(batch * max_chunks) * sizeof(WorkEntry);
+}
+
+// Host-side views of the work-list logic, for tests: the sort bin of a range, and which list item every
+// streaming wave takes under every ticket.
+int decode_list_sort_bin(int tokens, int chunk_tokens)
+{
+    return tokens > 0 ? sort_bin(tokens, sort_bins_per_page(chunk_tokens)) : kSortBins;
+}
+
+unsigned decode_ticket_map(unsigned n_entries, unsigned n_long_entries, unsigned hkv, unsigned n_workgroups,
+                           int* items, size_t capacity)
+{
+    const TicketSpace ts = make_ticket_space(n_entries, n_long_entries, hkv, n_workgroups);
+    for (unsigned t = 0; t < ts.n_tickets && ((size_t)t + 1) * 2 * kWaves <= capacity; ++t)
+        for (int w = 0; w < kWaves; ++w) {
+            unsigned idx;
+            bool grouped;
+            const bool valid = ticket_index(ts, t, w, idx, grouped);
+            items[((size_t)t * kWaves + w) * 2] = valid ? (int)idx : -1;
+            items[((size_t)t * kWaves + w) * 2 + 1] = grouped ? 1 : 0;
+        }
+    return ts.n_tickets;
 }
 
 hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s)

@@ -96,6 +96,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
 hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s);
 size_t decode_workspace_bytes(long long batch, long long max_chunks);
 bool decode_mfma_supports(const DecodeParams& p, bool bf16);
+int decode_list_sort_bin(int tokens, int chunk_tokens);
+unsigned decode_ticket_map(unsigned n_entries, unsigned n_long_entries, unsigned hkv, unsigned n_workgroups,
+                           int* items, size_t capacity);
 hipError_t launch_merge(const MergeParams& p, hipStream_t s);
 hipError_t launch_gather(const DecodeParams& p, bool bf16, int seq, void* k_out, void* v_out, hipStream_t s);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
