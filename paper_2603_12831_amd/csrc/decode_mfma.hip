@@ -533,7 +533,7 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
             if (p.part_o) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
         }
-        if (p.part_lse && d == 0) __builtin_nontemporal_store(lse, p.part_lse + prow0 + g);
+        if (p.part_lse && d == 0) p.part_lse[prow0 + g] = lse;         // 4 G bytes: a plain store, so that the L2 can fill the line
         if (final_row) {
             if (p.out_bf16) {
                 uint2 pk;
@@ -881,8 +881,11 @@ __device__ __forceinline__ void persistent_body(
     // wave's loads holds back its waits on younger loads; the writer has no loads to wait for (measured:
     // 0.5-2 % on batches of short items, nothing on long ones).  It meets the streaming waves at one
     // barrier per ticket; the combine areas alternate, so it works on ticket k while the others stream
-    // ticket k+1.  The partial rows carry the non-temporal hint: plain stores of these few bytes (0.5 % of
-    // the traffic) cost 3-4 % of the read rate on long contexts with many chunks, whichever wave issues them.
+    // ticket k+1.  The partial O rows (whole 128-byte lines) carry the non-temporal hint: plain stores of
+    // these few bytes (0.5 % of the traffic) cost 3-4 % of the read rate on long contexts with many chunks,
+    // whichever wave issues them.  An item's LSE values are 4 G bytes of a line that several items share:
+    // they go out as plain stores, which the L2 gathers (with the hint each is a partial-line write to
+    // memory: 1-1.5 % of the launch on configs 3 and 5).
     if (writer) {
         store_empty_share();
         lds_barrier();
