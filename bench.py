@@ -34,7 +34,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per decode-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
 # profiles/), scaled by the factor the same counters show for the plain copy kernel; None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg3-gqa-b256": 1997.0e6,      # profiles/decode_mfma_persistent_cfg3_pmc.md
+MEASURED_TRAFFIC_BYTES = {"cfg3-gqa-b256": 1996.7e6,      # profiles/decode_mfma_persistent_cfg3_pmc.md
                           "cfg2-mha-b64": 2327.6e6,       # profiles/decode_mfma_persistent_cfg2_cfg4_cfg5_pmc.md
                           "cfg4-hybrid-32ls-224be": 322.0e6, "cfg5-long-b32-L32768": 4337.0e6}
 
