@@ -48,6 +48,8 @@
 //     cannot end up last.  A fifth wave combines the four streaming waves' states
 //     and does all global stores, one item behind them.  Short ranges, when there
 //     are many, are taken four at a time, one whole item per wave.
+#include <mutex>
+
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -1101,25 +1103,57 @@ hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_
     return hipGetLastError();
 }
 
+namespace {
+
+// What a launch needs to know about the current device, found out once per device: the number of CUs, and
+// that the persistent kernel fits a CU even with its largest LDS request (G = 16), for which both kernels
+// are given the large LDS window.  Later calls only look the entry up.
+struct DeviceFacts { int cus; hipError_t status; bool known; };
+
+hipError_t device_facts(int& cus)
+{
+    constexpr int kMaxDevices = 64;
+    static DeviceFacts facts[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    DeviceFacts& f = facts[dev];
+    if (!f.known) {
+        f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
+        if (f.status == hipSuccess)
+            f.status = hipFuncSetAttribute((const void*)decode_mfma_persistent_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
+        if (f.status == hipSuccess && lds_g > 64 * 1024)
+            f.status = hipFuncSetAttribute((const void*)decode_mfma_grid_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_g);
+        int per_cu = 0;
+        if (f.status == hipSuccess)
+            f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel,
+                                                                    kPersistentThreads, lds_p);
+        if (f.status == hipSuccess && (per_cu < 1 || f.cus < 1)) f.status = hipErrorLaunchOutOfResources;
+        f.known = true;
+    }
+    cus = f.cus;
+    return f.status;
+}
+
+}  // namespace
+
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s)
 {
     const size_t lds = lds_bytes(p.group, workspace != nullptr);
-    if (lds > 64 * 1024) {                                 // G = 16 only: ask for the larger LDS window
-        hipError_t ea = hipFuncSetAttribute(workspace ? (const void*)decode_mfma_persistent_kernel
-                                                      : (const void*)decode_mfma_grid_kernel,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (ea != hipSuccess) return ea;
-    }
+    int cus = 0;
+    hipError_t e = device_facts(cus);
+    if (e != hipSuccess) return e;
     if (!workspace) {
         const unsigned grid = (unsigned)((long long)p.batch * p.max_chunks * p.hkv);
         hipLaunchKernelGGL(decode_mfma_grid_kernel, dim3(grid), dim3(kThreads), lds, s, p, p.block_table);
         return hipGetLastError();
     }
-    int dev = 0, cus = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
     unsigned* header = static_cast<unsigned*>(workspace);
     WorkEntry* entries = reinterpret_cast<WorkEntry*>(header + kHeaderWords);
     if (!planned) {
@@ -1130,10 +1164,6 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     // per CU already, and a CU serves its oldest waves first: a second and third workgroup get a
     // fraction of the first one's bandwidth, start late and finish late, which costs more at both ends
     // of the launch than their overlap gains in between (measured on every configuration).
-    int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel, kPersistentThreads, lds);
-    if (e != hipSuccess) return e;
-    if (per_cu < 1) return hipErrorLaunchOutOfResources;
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p,
