@@ -75,7 +75,8 @@ typedef enum {
     OMNI_ERR_SHAPE = -2,       /* non-positive size, G not integral, bad chunking */
     OMNI_ERR_DTYPE = -3,       /* dtype value not known                           */
     OMNI_ERR_UNSUPPORTED = -4, /* valid but outside the supported set             */
-    OMNI_ERR_LAUNCH = -5       /* HIP reported an error at launch                 */
+    OMNI_ERR_LAUNCH = -5,      /* HIP reported an error at launch                 */
+    OMNI_ERR_TOO_LARGE = -6    /* problem exceeds a fixed limit of the entry point */
 } omni_status;
 
 typedef enum { OMNI_F32 = 0, OMNI_BF16 = 1 } omni_dtype;
@@ -143,6 +144,22 @@ typedef struct {
  * LAUNCH.  A batch of zero is OK and does nothing.
  */
 omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream);
+
+/*
+ * omni_paged_decode_attn for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * results and the same kernels in their persistent form, but the work list lives in a scratch array of
+ * OMNI_STATIC_SCRATCH_BYTES that is part of the library (one copy per GPU, held until the process ends);
+ * a->workspace, workspace_bytes and workspace_planned are ignored and the list is rebuilt by every call.
+ * The call allocates nothing and frees nothing.  Limit: omni_decode_workspace_bytes(batch, max_chunks)
+ * must not exceed OMNI_STATIC_SCRATCH_BYTES (batch * max_chunks <= 131068), else OMNI_ERR_TOO_LARGE and
+ * nothing is launched.  Every call on a GPU uses that GPU's one array (each call rewrites all of it that
+ * it reads): calls that may overlap in time on one GPU (different streams) race and must be ordered by the
+ * caller, or use omni_paged_decode_attn with workspaces of their own.  Other errors as
+ * omni_paged_decode_attn.
+ */
+#define OMNI_STATIC_SCRATCH_BYTES (2u * 1024u * 1024u)
+omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_stream);
 
 /* Bytes of workspace the persistent form needs for this batch and chunk stride (0 if either is <= 0). */
 uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks);

@@ -19,8 +19,10 @@ LIB_PATH = os.path.join(_HERE, "libomni_attn.so")
 OMNI_F32, OMNI_BF16 = 0, 1
 OMNI_KERNEL_AUTO, OMNI_KERNEL_VECTOR, OMNI_KERNEL_MFMA = 0, 1, 2
 OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OMNI_ERR_LAUNCH = 0, -1, -2, -3, -4, -5
+OMNI_ERR_TOO_LARGE = -6
+OMNI_STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
 
-EXPORTS = ("omni_paged_decode_attn", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
+EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
            "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
@@ -91,6 +93,8 @@ def load_library() -> ctypes.CDLL:
         vp = ctypes.c_void_p
         lib.omni_paged_decode_attn.argtypes = [ctypes.POINTER(omni_decode_args), vp]
         lib.omni_paged_decode_attn.restype = ctypes.c_int
+        lib.omni_paged_decode_attn_static.argtypes = [ctypes.POINTER(omni_decode_args), vp]
+        lib.omni_paged_decode_attn_static.restype = ctypes.c_int
         lib.omni_decode_plan.argtypes = [ctypes.POINTER(omni_decode_args), vp]
         lib.omni_decode_plan.restype = ctypes.c_int
         lib.omni_decode_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
@@ -222,6 +226,13 @@ def omni_paged_decode_attn_raw(args: omni_decode_args, stream=None, check: bool 
     st = load_library().omni_paged_decode_attn(ctypes.byref(args), _stream_ptr(stream))
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_paged_decode_attn")
+    return st
+
+
+def omni_paged_decode_attn_static(args: omni_decode_args, stream=None, check: bool = True) -> int:
+    st = load_library().omni_paged_decode_attn_static(ctypes.byref(args), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_paged_decode_attn_static")
     return st
 
 

@@ -1,6 +1,8 @@
 // C ABI of libomni_attn: argument checks, flattening, kernel choice.
 #include <limits.h>
 
+#include <mutex>
+
 #include "omni_internal.hpp"
 
 using namespace omni;
@@ -48,11 +50,9 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
     return OMNI_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
+// The decode call behind both of its entry points: `ws` / `ws_bytes` is the work-list scratch to use
+// (the caller's workspace, or the library's own array), `planned` whether it already holds the list.
+omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_bytes, bool planned, void* hip_stream)
 {
     DecodeParams p;
     omni_status st = flatten(a, p, true);
@@ -65,13 +65,66 @@ omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
     bool mfma = decode_mfma_supports(p, bf16);
     if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return OMNI_ERR_UNSUPPORTED;
     if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
-    void* ws = mfma ? a->workspace : nullptr;
+    void* ws = mfma ? ws_given : nullptr;
     if (ws) {
-        if (a->workspace_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
+        if (ws_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return OMNI_ERR_SHAPE;
     }
-    hipError_t e = mfma ? launch_decode_mfma(p, ws, a->workspace_planned != 0, s) : launch_decode_vector(p, bf16, s);
+    hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
+}  // namespace
+
+// Work-list scratch of omni_paged_decode_attn_static: one array per GPU, part of the loaded code object, so
+// no call ever allocates it.  In host code the name below is only a handle; the array's device address is
+// asked for once per device (static_scratch) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[OMNI_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of `scratch` on the current device (every GPU has its own copy at its own address).
+hipError_t static_scratch(void*& ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static void* ptrs[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* found = nullptr;
+        e = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!found) return hipErrorInvalidSymbol;
+        ptrs[dev] = found;
+    }
+    ptr = ptrs[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
+{
+    if (!a) return OMNI_ERR_NULL;
+    return decode_attn(a, a->workspace, a->workspace_bytes, a->workspace_planned != 0, hip_stream);
+}
+
+omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_stream)
+{
+    if (!a) return OMNI_ERR_NULL;
+    if (a->batch > 0 && a->max_chunks > 0 &&
+        decode_workspace_bytes(a->batch, a->max_chunks) > (size_t)OMNI_STATIC_SCRATCH_BYTES)
+        return OMNI_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    if (static_scratch(ws) != hipSuccess) return OMNI_ERR_LAUNCH;
+    // the list is always rebuilt: the array is shared by every call on this GPU
+    return decode_attn(a, ws, OMNI_STATIC_SCRATCH_BYTES, false, hip_stream);
 }
 
 omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream)
@@ -228,6 +281,7 @@ const char* omni_status_string(omni_status s)
         case OMNI_ERR_DTYPE: return "OMNI_ERR_DTYPE: unknown dtype";
         case OMNI_ERR_UNSUPPORTED: return "OMNI_ERR_UNSUPPORTED: shape outside the supported set";
         case OMNI_ERR_LAUNCH: return "OMNI_ERR_LAUNCH: HIP launch failed";
+        case OMNI_ERR_TOO_LARGE: return "OMNI_ERR_TOO_LARGE: batch x max_chunks exceeds the library's static scratch";
     }
     return "OMNI_ERR_?: unknown status";
 }
