@@ -27,7 +27,9 @@
  * General rules
  *   - Every data pointer is DEVICE memory owned by the caller.  The library
  *     allocates nothing, frees nothing and keeps no state between calls; the
- *     only scratch it ever uses is the optional workspace the caller passes.
+ *     only scratch it ever uses is the optional workspace the caller passes
+ *     (omni_paged_decode_attn_static: a fixed array of its own instead).
+ *   - q, the pools, part_o and out_o must be 16-byte aligned (checked: SHAPE).
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and return without synchronising.
  *   - The return value reports what the host can see: NULL pointers, bad
@@ -88,6 +90,15 @@ typedef enum {
     OMNI_KERNEL_MFMA = 2       /* matrix-core kernel: bf16, head_dim 128 (else UNSUPPORTED)      */
 } omni_kernel;
 
+/* One source of partial rows (for the merge, and for the decode call's fused form). */
+typedef struct omni_partial_src_s {
+    const float*   o;                  /* [n_rows, num_q_heads, head_dim] fp32                 */
+    const float*   lse;                /* [n_rows, num_q_heads] fp32, natural log              */
+    const int32_t* row_offsets;        /* [batch+1] CSR: rows of sequence i are
+                                          row_offsets[i] .. row_offsets[i+1]-1; NULL = dense   */
+    int32_t        dense_rows_per_seq; /* dense: rows i*n .. i*n+n-1 belong to sequence i      */
+} omni_partial_src;
+
 typedef struct {
     /* problem shape */
     int32_t batch, num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq;
@@ -112,28 +123,51 @@ typedef struct {
     float* part_o;                 /* [batch, max_chunks, num_q_heads, head_dim] fp32; may be
                                       NULL if out_o is given and max_chunks == 1              */
     float* part_lse;               /* [batch, max_chunks, num_q_heads] fp32                   */
-    void*  out_o;                  /* optional [batch, num_q_heads, head_dim] of out_dtype:   */
-    int32_t out_dtype;             /*   with max_chunks == 1 the single chunk's O is also     */
-    float* out_lse;                /*   written here as the final row (and LSE to out_lse if  */
-                                   /*   not NULL; an empty range writes O = 0, LSE = -inf)    */
+    /* Final rows.  With out_o, a sequence whose (clamped) range fits one chunk - its only possibly
+     * non-empty chunk is chunk 0 - gets its final row from this call: O to out_o [batch, num_q_heads,
+     * head_dim] of out_dtype, LSE to out_lse if not NULL (an empty range: O = 0, LSE = -inf).  Such a
+     * sequence writes no partial O, and its part_lse slots read -inf (with max_chunks == 1 and partial
+     * buffers given, the partial is kept as well).  The other sequences write partials as without out_o
+     * and their out_o rows are left alone; seq_final tells which is which.                         */
+    void*  out_o;
+    int32_t out_dtype;
+    float* out_lse;
     int32_t kernel;                /* omni_kernel                                             */
     /* optional scratch for the matrix-core kernel's work list (device memory, caller-owned,
-     * at least omni_decode_workspace_bytes(batch, max_chunks) bytes, 16-byte aligned, contents
-     * need not survive between calls).  With it the kernel runs in its persistent form: non-empty
-     * chunks are listed longest-first and drawn by resident workgroups.  NULL selects the plain
-     * grid form.  Two calls that may overlap in time (different streams) need distinct
+     * at least omni_decode_workspace_bytes(batch, max_chunks, num_kv_heads) bytes, 16-byte aligned,
+     * contents need not survive between calls).  With it the kernel runs in its persistent form:
+     * non-empty chunks are listed longest-first and drawn by resident workgroups.  NULL selects the
+     * plain grid form.  Two calls that may overlap in time (different streams) need distinct
      * workspaces.  The vector kernel ignores it.  The 32-bit word at byte 20 of a workspace that
      * holds a list is a diagnostic: the list build zeroes it and a wave that gives a launch up
      * (its bounded wait for the next work item ran out, about a second) adds one; it stays zero
-     * in every healthy run, and a non-zero value means rows of that launch are missing.         */
+     * in every healthy run, and a non-zero value means rows of some launch since then are missing
+     * (omni_decode_abandoned_waves reads and clears it).                                         */
     void*    workspace;
     uint64_t workspace_bytes;
     /* non-zero: the workspace already holds the work list of exactly these ranges and this
      * chunking, written by omni_decode_plan (or by an earlier call with the same ranges): the
      * list is reused instead of rebuilt.  The list depends only on batch, ctx_begin, ctx_end,
-     * max_blocks_per_seq, chunk_tokens and max_chunks, so one plan serves the attention calls
-     * of every layer of a decoding iteration.                                                 */
+     * max_blocks_per_seq, chunk_tokens, max_chunks and num_kv_heads, so one plan serves the
+     * attention calls of every layer of a decoding iteration.                                 */
     int32_t  workspace_planned;
+    /* optional [batch] int32 output: 1 where this call wrote the sequence's final row to out_o /
+     * out_lse, 0 where its partial rows still have to be merged (omni_merge_partials_masked takes
+     * the array as its skip list).  Required when out_o is given with max_chunks > 1 and
+     * fuse_merge == 0.                                                                         */
+    int32_t* seq_final;
+    /* non-zero: every sequence's final row comes out of this call (persistent form of the
+     * matrix-core kernel only: a workspace is required, else UNSUPPORTED; out_o is required).
+     * Sequences with several non-empty chunks still write their partial rows to part_o / part_lse
+     * (scratch in this form: which of their rows a later reader finds is unspecified); the
+     * workgroup that finishes a (sequence, kv head)'s last chunk merges them in chunk order.
+     * ext_srcs[0 .. n_ext_srcs) (host array of up to 3 sources, copied during the call; NULL / 0 =
+     * none) are rows computed elsewhere for these sequences - the attention rows that come back
+     * through the output queue - and are folded into the final rows by the same rule, so that a
+     * hybrid batch needs no separate merge launch.                                             */
+    int32_t  fuse_merge;
+    const struct omni_partial_src_s* ext_srcs;
+    int32_t  n_ext_srcs;
 } omni_decode_args;
 
 /*
@@ -151,8 +185,9 @@ omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream);
  * results and the same kernels in their persistent form, but the work list lives in a scratch array of
  * OMNI_STATIC_SCRATCH_BYTES that is part of the library (one copy per GPU, held until the process ends);
  * a->workspace, workspace_bytes and workspace_planned are ignored and the list is rebuilt by every call.
- * The call allocates nothing and frees nothing.  Limit: omni_decode_workspace_bytes(batch, max_chunks)
- * must not exceed OMNI_STATIC_SCRATCH_BYTES (batch * max_chunks <= 131068), else OMNI_ERR_TOO_LARGE and
+ * The call allocates nothing and frees nothing.  Limit: omni_decode_workspace_bytes(batch, max_chunks,
+ * num_kv_heads) must not exceed OMNI_STATIC_SCRATCH_BYTES (2 MiB: 64 + 16 batch max_chunks + 4 batch
+ * num_kv_heads bytes, e.g. batch * max_chunks <= 100 000 at 8 kv heads), else OMNI_ERR_TOO_LARGE and
  * nothing is launched.  Every call on a GPU uses that GPU's one array (each call rewrites all of it that
  * it reads): calls that may overlap in time on one GPU (different streams) race and must be ordered by the
  * caller, or use omni_paged_decode_attn with workspaces of their own.  Other errors as
@@ -161,8 +196,18 @@ omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream);
 #define OMNI_STATIC_SCRATCH_BYTES (2u * 1024u * 1024u)
 omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_stream);
 
-/* Bytes of workspace the persistent form needs for this batch and chunk stride (0 if either is <= 0). */
-uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks);
+/* Bytes of workspace the persistent form needs for this batch, chunk stride and kv-head count: the work
+ * list and one arrival counter per (sequence, kv head) (0 if any of them is <= 0). */
+uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks, int32_t num_kv_heads);
+
+/*
+ * Reads the diagnostic word of a workspace that holds a work list (see `workspace` above) into *count
+ * (host memory) and puts it back to zero: the number of waves that gave a launch up since the list was
+ * built or the word was last cleared; 0 in every healthy run, anything else means that rows of some
+ * launch in between were not written.  workspace = NULL means the static scratch of
+ * omni_paged_decode_attn_static on the current device.  Waits for the stream.  Errors: NULL, LAUNCH.
+ */
+omni_status omni_decode_abandoned_waves(void* workspace, uint32_t* count, void* hip_stream);
 
 /*
  * Build the work list for `a` into a->workspace on the stream, without computing attention: the
@@ -171,15 +216,6 @@ uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks);
  * workspace_planned.  Errors: as omni_paged_decode_attn, plus NULL if there is no workspace.
  */
 omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream);
-
-/* One source of partial rows for the merge. */
-typedef struct {
-    const float*   o;                  /* [n_rows, num_q_heads, head_dim] fp32                 */
-    const float*   lse;                /* [n_rows, num_q_heads] fp32, natural log              */
-    const int32_t* row_offsets;        /* [batch+1] CSR: rows of sequence i are
-                                          row_offsets[i] .. row_offsets[i+1]-1; NULL = dense   */
-    int32_t        dense_rows_per_seq; /* dense: rows i*n .. i*n+n-1 belong to sequence i      */
-} omni_partial_src;
 
 /*
  * Merge the partials of every (sequence, query head) found in srcs[0..n_srcs)
@@ -194,6 +230,12 @@ omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head
                                 const omni_partial_src* srcs, int32_t n_srcs,
                                 void* out_o, int32_t out_dtype, float* out_lse,
                                 void* hip_stream);
+/* The same, leaving alone the out_o / out_lse rows of every sequence i with skip[i] != 0 (device int32
+ * [batch]; NULL = none): the seq_final array of a decode call that already wrote those final rows. */
+omni_status omni_merge_partials_masked(int32_t batch, int32_t num_q_heads, int32_t head_dim,
+                                       const omni_partial_src* srcs, int32_t n_srcs, const int32_t* skip,
+                                       void* out_o, int32_t out_dtype, float* out_lse,
+                                       void* hip_stream);
 
 /*
  * KV-cache data movement around the decode step.

@@ -22,7 +22,8 @@ OMNI_OK, OMNI_ERR_NULL, OMNI_ERR_SHAPE, OMNI_ERR_DTYPE, OMNI_ERR_UNSUPPORTED, OM
 OMNI_ERR_TOO_LARGE = -6
 OMNI_STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
 
-EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_decode_workspace_bytes", "omni_decode_plan", "omni_merge_partials",
+EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_decode_workspace_bytes", "omni_decode_plan",
+           "omni_decode_abandoned_waves", "omni_merge_partials", "omni_merge_partials_masked",
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
            "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
@@ -33,6 +34,11 @@ class OmniError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s failed: %s" % (where, omni_status_string(status)))
+
+
+class omni_partial_src(ctypes.Structure):
+    _fields_ = [("o", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("row_offsets", ctypes.c_void_p),
+                ("dense_rows_per_seq", ctypes.c_int32)]
 
 
 class omni_decode_args(ctypes.Structure):
@@ -48,6 +54,8 @@ class omni_decode_args(ctypes.Structure):
         ("kernel", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_uint64),
         ("workspace_planned", ctypes.c_int32),
+        ("seq_final", ctypes.c_void_p), ("fuse_merge", ctypes.c_int32),
+        ("ext_srcs", ctypes.POINTER(omni_partial_src)), ("n_ext_srcs", ctypes.c_int32),
     ]
 
 
@@ -74,11 +82,6 @@ class omni_host_attn_args(ctypes.Structure):
                 ("n_threads", ctypes.c_int32)]
 
 
-class omni_partial_src(ctypes.Structure):
-    _fields_ = [("o", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("row_offsets", ctypes.c_void_p),
-                ("dense_rows_per_seq", ctypes.c_int32)]
-
-
 _lib = None
 
 
@@ -97,8 +100,14 @@ def load_library() -> ctypes.CDLL:
         lib.omni_paged_decode_attn_static.restype = ctypes.c_int
         lib.omni_decode_plan.argtypes = [ctypes.POINTER(omni_decode_args), vp]
         lib.omni_decode_plan.restype = ctypes.c_int
-        lib.omni_decode_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        lib.omni_decode_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.omni_decode_workspace_bytes.restype = ctypes.c_uint64
+        lib.omni_decode_abandoned_waves.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
+        lib.omni_decode_abandoned_waves.restype = ctypes.c_int
+        lib.omni_merge_partials_masked.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                                   ctypes.POINTER(omni_partial_src), ctypes.c_int32, vp, vp,
+                                                   ctypes.c_int32, vp, vp]
+        lib.omni_merge_partials_masked.restype = ctypes.c_int
         lib.omni_merge_partials.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                             ctypes.POINTER(omni_partial_src), ctypes.c_int32, vp,
                                             ctypes.c_int32, vp, vp]
@@ -171,7 +180,8 @@ def omni_status_string(status: int) -> str:
 def make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
                      chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None, out_o=None,
                      out_lse=None, kernel: int = OMNI_KERNEL_AUTO, workspace=None,
-                     workspace_planned: bool = False) -> omni_decode_args:
+                     workspace_planned: bool = False, seq_final=None, fuse_merge: bool = False,
+                     ext_srcs: Optional[Sequence["PartialSrc"]] = None) -> omni_decode_args:
     """Fill the C argument struct from tensors (shapes are taken from the tensors)."""
     a = omni_decode_args()
     a.batch, a.num_q_heads, a.head_dim = q.shape
@@ -208,17 +218,27 @@ def make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_s
     a.workspace = _dev_ptr(workspace, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.workspace_planned = 1 if workspace_planned else 0
+    if seq_final is not None and seq_final.numel() != a.batch:
+        raise ValueError("seq_final must have one entry per sequence")
+    a.seq_final = _dev_ptr(seq_final, "seq_final", torch.int32)
+    a.fuse_merge = 1 if fuse_merge else 0
+    if ext_srcs:
+        a._ext_keepalive = make_partial_srcs(ext_srcs, a.batch, a.num_q_heads, a.head_dim)   # host array
+        a.ext_srcs = ctypes.cast(a._ext_keepalive, ctypes.POINTER(omni_partial_src))
+        a.n_ext_srcs = len(ext_srcs)
     return a
 
 
 def omni_paged_decode_attn(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, *, sm_scale: float,
                            chunk_tokens: int = 0, max_chunks: int = 1, part_o=None, part_lse=None,
                            out_o=None, out_lse=None, kernel: int = OMNI_KERNEL_AUTO, workspace=None,
-                           workspace_planned: bool = False, stream=None, check: bool = True) -> int:
+                           workspace_planned: bool = False, seq_final=None, fuse_merge: bool = False,
+                           ext_srcs=None, stream=None, check: bool = True) -> int:
     a = make_decode_args(q, k_pool, v_pool, block_table, ctx_begin, ctx_end, sm_scale=sm_scale,
                          chunk_tokens=chunk_tokens, max_chunks=max_chunks, part_o=part_o, part_lse=part_lse,
                          out_o=out_o, out_lse=out_lse, kernel=kernel, workspace=workspace,
-                         workspace_planned=workspace_planned)
+                         workspace_planned=workspace_planned, seq_final=seq_final, fuse_merge=fuse_merge,
+                         ext_srcs=ext_srcs)
     return omni_paged_decode_attn_raw(a, stream, check)
 
 
@@ -243,8 +263,17 @@ def omni_decode_plan(args: omni_decode_args, stream=None, check: bool = True) ->
     return st
 
 
-def omni_decode_workspace_bytes(batch: int, max_chunks: int) -> int:
-    return int(load_library().omni_decode_workspace_bytes(int(batch), int(max_chunks)))
+def omni_decode_workspace_bytes(batch: int, max_chunks: int, num_kv_heads: int) -> int:
+    return int(load_library().omni_decode_workspace_bytes(int(batch), int(max_chunks), int(num_kv_heads)))
+
+
+def omni_decode_abandoned_waves(workspace=None, stream=None) -> int:
+    """Reads and clears the diagnostic word of a work list (None: the library's static scratch)."""
+    n = ctypes.c_uint32(0)
+    st = load_library().omni_decode_abandoned_waves(_dev_ptr(workspace, "workspace"), ctypes.byref(n), _stream_ptr(stream))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_decode_abandoned_waves")
+    return int(n.value)
 
 
 PartialSrc = Tuple[torch.Tensor, torch.Tensor, Optional[torch.Tensor], int]
@@ -278,6 +307,23 @@ def omni_merge_partials(batch: int, num_q_heads: int, head_dim: int, srcs: Seque
                                             _dev_ptr(out_lse, "out_lse", torch.float32), _stream_ptr(stream))
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_merge_partials")
+    return st
+
+
+def omni_merge_partials_masked(batch: int, num_q_heads: int, head_dim: int, srcs: Sequence[PartialSrc], skip,
+                               out_o, out_lse=None, stream=None, check: bool = True) -> int:
+    """As omni_merge_partials; rows of sequences with skip[i] != 0 (int32 [batch] or None) are left alone."""
+    arr = make_partial_srcs(srcs, batch, num_q_heads, head_dim)
+    if out_o.numel() != batch * num_q_heads * head_dim:
+        raise ValueError("out_o has the wrong size")
+    if skip is not None and skip.numel() != batch:
+        raise ValueError("skip must have one entry per sequence")
+    st = load_library().omni_merge_partials_masked(batch, num_q_heads, head_dim, arr, len(srcs),
+                                                   _dev_ptr(skip, "skip", torch.int32),
+                                                   _dev_ptr(out_o, "out_o"), _dtype_code(out_o, "out_o"),
+                                                   _dev_ptr(out_lse, "out_lse", torch.float32), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_merge_partials_masked")
     return st
 
 

@@ -29,11 +29,29 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
     if (a->batch > 65535 || a->max_chunks > 65535) return OMNI_ERR_UNSUPPORTED;
     if ((long long)a->max_blocks_per_seq * kBlockSize > INT_MAX / 2) return OMNI_ERR_UNSUPPORTED;
     if (!a->q || !a->k_pool || !a->v_pool || !a->block_table || !a->ctx_end) return OMNI_ERR_NULL;
+    if (a->n_ext_srcs < 0 || a->n_ext_srcs > 3) return OMNI_ERR_SHAPE;
     if (need_outputs) {
         if (!dtype_ok(a->out_dtype) && a->out_o) return OMNI_ERR_DTYPE;
         const bool partials = a->part_o && a->part_lse;
         if ((a->part_o == nullptr) != (a->part_lse == nullptr)) return OMNI_ERR_NULL;
+        // without partial buffers every row must be a final row: a single chunk slot
         if (!partials && !(a->out_o && a->max_chunks == 1)) return OMNI_ERR_NULL;
+        // final rows of part of the batch only: the caller must be told which
+        if (a->out_o && a->max_chunks > 1 && !a->fuse_merge && !a->seq_final) return OMNI_ERR_NULL;
+        if (a->fuse_merge && !a->out_o) return OMNI_ERR_NULL;
+        if (a->n_ext_srcs > 0) {
+            if (!a->fuse_merge) return OMNI_ERR_SHAPE;
+            if (!a->ext_srcs) return OMNI_ERR_NULL;
+            for (int i = 0; i < a->n_ext_srcs; ++i) {
+                if (!a->ext_srcs[i].o || !a->ext_srcs[i].lse) return OMNI_ERR_NULL;
+                if (!a->ext_srcs[i].row_offsets && a->ext_srcs[i].dense_rows_per_seq < 0) return OMNI_ERR_SHAPE;
+            }
+        }
+        // the kernels move q and the rows in 16-byte pieces (bf16 final rows in 8-byte ones)
+        auto misaligned = [](const void* ptr) { return reinterpret_cast<uintptr_t>(ptr) % 16 != 0; };
+        if (misaligned(a->q) || misaligned(a->k_pool) || misaligned(a->v_pool) || misaligned(a->part_o) ||
+            misaligned(a->out_o))
+            return OMNI_ERR_SHAPE;
     }
     p.batch = a->batch; p.hq = a->num_q_heads; p.hkv = a->num_kv_heads; p.d = a->head_dim;
     p.max_blocks = a->max_blocks_per_seq; p.group = a->num_q_heads / a->num_kv_heads;
@@ -44,9 +62,14 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
     p.chunk_tokens = a->chunk_tokens ? a->chunk_tokens : a->max_blocks_per_seq * kBlockSize;
     p.max_chunks = a->max_chunks;
     p.part_o = a->part_o; p.part_lse = a->part_lse;
-    p.out_o = (a->max_chunks == 1) ? a->out_o : nullptr;
+    p.out_o = need_outputs ? a->out_o : nullptr;
     p.out_bf16 = a->out_dtype == OMNI_BF16;
     p.out_lse = p.out_o ? a->out_lse : nullptr;
+    p.seq_final = need_outputs ? a->seq_final : nullptr;
+    p.fuse = (need_outputs && a->fuse_merge) ? 1 : 0;
+    p.n_ext = p.fuse ? a->n_ext_srcs : 0;
+    for (int i = 0; i < 3; ++i)
+        p.ext[i] = i < p.n_ext ? a->ext_srcs[i] : omni_partial_src{nullptr, nullptr, nullptr, 0};
     return OMNI_OK;
 }
 
@@ -67,9 +90,10 @@ omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_b
     if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
     void* ws = mfma ? ws_given : nullptr;
     if (ws) {
-        if (ws_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
+        if (ws_bytes < decode_workspace_bytes(p.batch, p.max_chunks, p.hkv)) return OMNI_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return OMNI_ERR_SHAPE;
     }
+    if (p.fuse && !ws) return OMNI_ERR_UNSUPPORTED;        // only the persistent form finishes every sequence
     hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
@@ -118,13 +142,26 @@ omni_status omni_paged_decode_attn(const omni_decode_args* a, void* hip_stream)
 omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_stream)
 {
     if (!a) return OMNI_ERR_NULL;
-    if (a->batch > 0 && a->max_chunks > 0 &&
-        decode_workspace_bytes(a->batch, a->max_chunks) > (size_t)OMNI_STATIC_SCRATCH_BYTES)
+    if (a->batch > 0 && a->max_chunks > 0 && a->num_kv_heads > 0 &&
+        decode_workspace_bytes(a->batch, a->max_chunks, a->num_kv_heads) > (size_t)OMNI_STATIC_SCRATCH_BYTES)
         return OMNI_ERR_TOO_LARGE;
     void* ws = nullptr;
     if (static_scratch(ws) != hipSuccess) return OMNI_ERR_LAUNCH;
     // the list is always rebuilt: the array is shared by every call on this GPU
     return decode_attn(a, ws, OMNI_STATIC_SCRATCH_BYTES, false, hip_stream);
+}
+
+omni_status omni_decode_abandoned_waves(void* workspace, uint32_t* count, void* hip_stream)
+{
+    if (!count) return OMNI_ERR_NULL;
+    void* ws = workspace;
+    if (!ws && static_scratch(ws) != hipSuccess) return OMNI_ERR_LAUNCH;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    char* word = static_cast<char*>(ws) + 20;
+    if (hipMemcpyAsync(count, word, sizeof(uint32_t), hipMemcpyDeviceToHost, s) != hipSuccess) return OMNI_ERR_LAUNCH;
+    if (hipStreamSynchronize(s) != hipSuccess) return OMNI_ERR_LAUNCH;
+    if (*count != 0 && hipMemsetAsync(word, 0, sizeof(uint32_t), s) != hipSuccess) return OMNI_ERR_LAUNCH;
+    return OMNI_OK;
 }
 
 omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream)
@@ -133,22 +170,30 @@ omni_status omni_decode_plan(const omni_decode_args* a, void* hip_stream)
     omni_status st = flatten(a, p, false);
     if (st != OMNI_OK) return st;
     if (!a->workspace) return OMNI_ERR_NULL;
-    if (a->workspace_bytes < decode_workspace_bytes(p.batch, p.max_chunks)) return OMNI_ERR_SHAPE;
+    if (a->workspace_bytes < decode_workspace_bytes(p.batch, p.max_chunks, p.hkv)) return OMNI_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(a->workspace) % 16 != 0) return OMNI_ERR_SHAPE;
     if (p.batch == 0) return OMNI_OK;
     hipError_t e = launch_decode_plan(p, a->workspace, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
 
-uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks)
+uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks, int32_t num_kv_heads)
 {
-    if (batch <= 0 || max_chunks <= 0) return 0;
-    return decode_workspace_bytes(batch, max_chunks);
+    if (batch <= 0 || max_chunks <= 0 || num_kv_heads <= 0) return 0;
+    return decode_workspace_bytes(batch, max_chunks, num_kv_heads);
 }
 
 omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head_dim,
                                 const omni_partial_src* srcs, int32_t n_srcs,
                                 void* out_o, int32_t out_dtype, float* out_lse, void* hip_stream)
+{
+    return omni_merge_partials_masked(batch, num_q_heads, head_dim, srcs, n_srcs, nullptr, out_o, out_dtype, out_lse,
+                                      hip_stream);
+}
+
+omni_status omni_merge_partials_masked(int32_t batch, int32_t num_q_heads, int32_t head_dim,
+                                       const omni_partial_src* srcs, int32_t n_srcs, const int32_t* skip,
+                                       void* out_o, int32_t out_dtype, float* out_lse, void* hip_stream)
 {
     if (batch < 0 || num_q_heads <= 0 || n_srcs < 1 || n_srcs > 4) return OMNI_ERR_SHAPE;
     if (head_dim != 64 && head_dim != 128) return OMNI_ERR_SHAPE;
@@ -162,7 +207,7 @@ omni_status omni_merge_partials(int32_t batch, int32_t num_q_heads, int32_t head
     }
     for (int i = n_srcs; i < 4; ++i) p.src[i] = omni_partial_src{nullptr, nullptr, nullptr, 0};
     p.n_srcs = n_srcs; p.batch = batch; p.hq = num_q_heads; p.d = head_dim;
-    p.out_bf16 = out_dtype == OMNI_BF16; p.out_o = out_o; p.out_lse = out_lse;
+    p.out_bf16 = out_dtype == OMNI_BF16; p.out_o = out_o; p.out_lse = out_lse; p.skip = skip;
     hipError_t e = launch_merge(p, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }

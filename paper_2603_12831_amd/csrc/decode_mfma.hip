@@ -70,7 +70,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kSortBins = 256;
 
-struct alignas(16) WorkEntry { int seq, chunk, cb, ce; };   // a non-empty token range [cb, ce) of one chunk
+// A non-empty token range [cb, ce) of one chunk; `chunk` carries the chunk index in its low 16 bits and the
+// number of non-empty chunks of the sequence in its high 16 bits (both are at most 65535).
+struct alignas(16) WorkEntry { int seq, chunk, cb, ce; };
 
 struct StepRegs {            // raw V registers of one 32-token step (pages A and B); K waits in LDS
     u32x4 va[4], vb[4];
@@ -86,6 +88,7 @@ typedef const __attribute__((address_space(1))) void global_void;
 
 struct Item {                // wave-uniform description of a work item
     int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
+    int n_live;              // non-empty chunks of the item's sequence (the item's own included)
     int s0, ds;              // this wave's steps of the item: s0, s0 + ds, ... (ds = 1: the item is this wave's alone)
     const int* __restrict__ table;
 };
@@ -231,7 +234,7 @@ __device__ __forceinline__ void make_uniform(Item& it)
     it.seq = uniform(it.seq); it.chunk = uniform(it.chunk); it.kvh = uniform(it.kvh);
     it.cb = uniform(it.cb); it.ce = uniform(it.ce);
     it.lp_first = uniform(it.lp_first); it.lp_last = uniform(it.lp_last); it.n_steps = uniform(it.n_steps);
-    it.s0 = uniform(it.s0); it.ds = uniform(it.ds);
+    it.s0 = uniform(it.s0); it.ds = uniform(it.ds); it.n_live = uniform(it.n_live);
     const unsigned long long t = reinterpret_cast<unsigned long long>(it.table);
     const unsigned lo = (unsigned)uniform((int)(unsigned)t), hi = (unsigned)uniform((int)(unsigned)(t >> 32));
     it.table = reinterpret_cast<const int*>(((unsigned long long)hi << 32) | (unsigned long long)lo);
@@ -502,15 +505,165 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
+// Folds the rows that the sources of rows computed elsewhere hold for sequence `seq`, query head `head`
+// (dims d .. d+3) into (o, lse), which is this launch's own contribution (lse = -inf and o = 0: none).
+// The merge rule is the disjoint-union identity of Eq. 1 (as in the merge kernel: maximum first, then the
+// weights), rows eight at a time so that eight independent loads are in flight.
+__device__ __forceinline__ void fold_ext_rows(const DecodeParams& p, int seq, int head, int d, f32x4& o, float& lse)
+{
+    constexpr int kBatch = 8;
+    float m = lse;
+    for (int s = 0; s < p.n_ext; ++s) {
+        int r0, r1;
+        src_rows(p.ext[s], seq, r0, r1);
+        const float* l = p.ext[s].lse + head;
+        for (int r = r0; r < r1; r += kBatch) {
+            float v[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) v[u] = (r + u < r1) ? l[(long long)(r + u) * p.hq] : -INFINITY;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) m = fmaxf(m, v[u]);
+        }
+    }
+    if (m == -INFINITY) return;                                    // no weight anywhere: O = 0, LSE = -inf
+    float wsum = (lse == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((lse - m) * kLog2e);
+    f32x4 acc = o * wsum;
+    for (int s = 0; s < p.n_ext; ++s) {
+        int r0, r1;
+        src_rows(p.ext[s], seq, r0, r1);
+        const float* l = p.ext[s].lse + head;
+        const float* orow = p.ext[s].o + (long long)head * kD + d;
+        for (int r = r0; r < r1; r += kBatch) {
+            float w[kBatch];
+            f32x4 x[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const float v = (r + u < r1) ? l[(long long)(r + u) * p.hq] : -INFINITY;
+                w[u] = (v == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((v - m) * kLog2e);
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {                     // a row without weight is not read at all
+                x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (w[u] != 0.f) x[u] = *reinterpret_cast<const f32x4*>(orow + (long long)(r + u) * p.hq * kD);
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) { wsum += w[u]; acc += w[u] * x[u]; }
+        }
+    }
+    const float inv = 1.f / wsum;
+    o = acc * inv;
+    lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+}
+
+// four dims of a final row (row = sequence * Hq + head)
+__device__ __forceinline__ void store_final_quad(const DecodeParams& p, long long row, int d, f32x4 o, float lse)
+{
+    if (p.out_bf16) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_o) + row * kD + d) = pk;
+    } else {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(p.out_o) + row * kD + d) = o;
+    }
+    if (p.out_lse && d == 0) p.out_lse[row] = lse;
+}
+
+// What becomes of an item's rows: a partial row for a later merge; the sequence's final row (the item is
+// the sequence's only non-empty chunk); the final row after folding in the rows other sources hold for
+// the sequence.
+// kRowShared: a partial row that another workgroup of this launch will read (the fused form: whoever
+// finishes a sequence's last chunk merges them all).
+enum RowMode { kRowPartial = 0, kRowFinal = 1, kRowFinalFold = 2, kRowShared = 3 };
+
+__device__ __forceinline__ int row_mode(const DecodeParams& p, int n_live)
+{
+    if (p.out_o == nullptr) return kRowPartial;
+    if (n_live > 1) return p.fuse ? kRowShared : kRowPartial;
+    return p.n_ext > 0 ? kRowFinalFold : kRowFinal;
+}
+
+// Partial rows that cross from one workgroup to another inside a launch are stored and loaded at device
+// scope (each XCD has an L2 of its own; a device-scope store is written through it, a device-scope load
+// does not take a line another XCD may have changed from it), so no cache-wide write-back or invalidate is
+// needed: those cost a third of the read rate when issued per item.  `base` + `bytes` bound the buffer
+// resource, `off` is the lane's byte offset in it.
+__device__ __forceinline__ void store_shared4(float* base, int bytes, int off, f32x4 v)
+{
+    constexpr int kDeviceScopeNt = (1 << 4) | (1 << 1);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), byte_buffer(base, bytes), off, 0, kDeviceScopeNt);
+}
+__device__ __forceinline__ f32x4 load_shared4(const float* base, int bytes, int off)
+{
+    constexpr int kDeviceScope = 1 << 4;
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(byte_buffer(base, bytes), off, 0, kDeviceScope));
+}
+
+// The fused form's merge: the partial rows of chunks 0 .. n_live-1 of (sequence, kv head), written by this
+// and other workgroups of the launch, then whatever other sources hold for the sequence, into the final
+// rows of the G heads.  Chunk order, so the result does not depend on which workgroup came last.
+__device__ __forceinline__ void merge_chunks_and_store(const DecodeParams& p, int seq, int kvh, int n_live, int G,
+                                                       int tid, int nthreads)
+{
+    constexpr int kBatch = 8;
+    const long long chunk_rows = (long long)p.hq;                       // rows between consecutive chunks
+    const long long prow0 = (long long)seq * p.max_chunks * p.hq + (long long)kvh * G;
+    const long long orow0 = (long long)seq * p.hq + (long long)kvh * G;
+    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
+        const int g = idx >> 5, d = (idx & 31) * 4;
+        const float* l = p.part_lse + prow0 + g;
+        float m = -INFINITY;
+        for (int c = 0; c < n_live; c += kBatch) {
+            float v[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                v[u] = (c + u < n_live) ? __hip_atomic_load(l + (c + u) * chunk_rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                        : -INFINITY;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) m = fmaxf(m, v[u]);
+        }
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        float lse = -INFINITY;
+        if (m != -INFINITY) {
+            float wsum = 0.f;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < n_live; c += kBatch) {
+                float w[kBatch];
+                f32x4 x[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float v = (c + u < n_live) ? __hip_atomic_load(l + (c + u) * chunk_rows, __ATOMIC_RELAXED,
+                                                                         __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
+                    w[u] = (v == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((v - m) * kLog2e);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (w[u] != 0.f)
+                        x[u] = load_shared4(p.part_o + (prow0 + (c + u) * chunk_rows) * kD, G * kD * 4, (g * kD + d) * 4);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) { wsum += w[u]; acc += w[u] * x[u]; }
+            }
+            o = acc * (1.f / wsum);
+            lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+        }
+        if (p.n_ext > 0) fold_ext_rows(p, seq, kvh * G + g, d, o, lse);
+        store_final_quad(p, orow0 + g, d, o, lse);
+    }
+}
+
 // after a barrier: merge the states of waves w0 .. w1-1 with the log-sum-exp rule and write the item's rows
 // (only seq, chunk and kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn
 __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
-                                                  int tid, int nthreads, int w0 = 0, int w1 = kWaves)
+                                                  int tid, int nthreads, int mode, int w0 = 0, int w1 = kWaves)
 {
     const float* sh_acc = lds;
     const float* sh_m = lds + kWaves * G * kD;
     const float* sh_l = sh_m + kWaves * 16;
-    const bool final_row = p.out_o != nullptr;                 // only set when max_chunks == 1
+    const bool final_row = mode == kRowFinal || mode == kRowFinalFold;
+    // a final row is also kept as a partial one when the call has a single chunk slot and a partial buffer
+    const bool partial_row = !final_row || p.max_chunks == 1;
     const long long prow0 = ((long long)it.seq * p.max_chunks + it.chunk) * p.hq + (long long)it.kvh * G;
     const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
     for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
@@ -533,38 +686,41 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
             lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
-            if (p.part_o) __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
-        }
-        if (p.part_lse && d == 0) p.part_lse[prow0 + g] = lse;         // 4 G bytes: a plain store, so that the L2 can fill the line
-        if (final_row) {
-            if (p.out_bf16) {
-                uint2 pk;
-                pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
-                pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
-                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_o) + (orow0 + g) * kD + d) = pk;
-            } else {
-                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out_o) + (orow0 + g) * kD + d) = o;
+            if (p.part_o && partial_row) {
+                if (mode == kRowShared) store_shared4(p.part_o + prow0 * kD, G * kD * 4, (g * kD + d) * 4, o);
+                else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
             }
-            if (p.out_lse && d == 0) p.out_lse[orow0 + g] = lse;
+        }
+        // 4 G bytes: a plain store, so that the L2 can fill the line; the slot of a row that went out as a
+        // final row holds no partial
+        if (p.part_lse && d == 0) {
+            if (mode == kRowShared) __hip_atomic_store(p.part_lse + prow0 + g, lse, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else p.part_lse[prow0 + g] = partial_row ? lse : -INFINITY;
+        }
+        if (final_row) {
+            if (mode == kRowFinalFold) fold_ext_rows(p, it.seq, it.kvh * G + g, d, o, lse);
+            store_final_quad(p, orow0 + g, d, o, lse);
         }
     }
 }
 
-// rows of an empty range: LSE = -inf, final O = 0, partial O left unwritten; `heads` rows from `head0`
+// rows of an empty range: LSE = -inf, partial O left unwritten; `heads` rows from `head0`.  `final_here`:
+// the range is the sequence's whole (empty) range and the call writes final rows: O = 0 and LSE = -inf, or
+// whatever the other sources hold for the sequence.
 __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int chunk, int head0, int heads,
-                                            int tid, int nthreads)
+                                            int tid, int nthreads, bool final_here)
 {
-    const bool final_row = p.out_o != nullptr;
     const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + head0;
     const long long orow0 = (long long)seq * p.hq + head0;
-    for (int h = tid; h < heads; h += nthreads) {
-        if (p.part_lse) p.part_lse[prow0 + h] = -INFINITY;
-        if (final_row && p.out_lse) p.out_lse[orow0 + h] = -INFINITY;
-    }
-    if (final_row) {
-        for (int i = tid; i < heads * kD; i += nthreads) {
-            if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow0 * kD + i] = 0;
-            else static_cast<float*>(p.out_o)[orow0 * kD + i] = 0.f;
+    if (p.part_lse)
+        for (int h = tid; h < heads; h += nthreads) p.part_lse[prow0 + h] = -INFINITY;
+    if (final_here) {
+        for (int idx = tid; idx < heads * (kD / 4); idx += nthreads) {
+            const int g = idx >> 5, d = (idx & 31) * 4;
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            float lse = -INFINITY;
+            if (p.n_ext > 0) fold_ext_rows(p, seq, head0 + g, d, o, lse);
+            store_final_quad(p, orow0 + g, d, o, lse);
         }
     }
 }
@@ -586,8 +742,12 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     int b, e;
     seq_range(p, it.seq, b, e);
     chunk_range(p, b, e, it.chunk, it.cb, it.ce);
+    it.n_live = live_chunks(p, b, e);
+    if (p.seq_final && it.chunk == 0 && it.kvh == 0 && threadIdx.x == 0)
+        p.seq_final[it.seq] = (p.out_o != nullptr && it.n_live <= 1) ? 1 : 0;
     if (it.ce <= it.cb) {
-        store_empty(p, it.seq, it.chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads);
+        store_empty(p, it.seq, it.chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads,
+                    p.out_o != nullptr && it.chunk == 0);
         return;
     }
     finish_item(it, block_table, p.max_blocks);
@@ -609,13 +769,14 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
-    combine_and_store(p, it, lds, p.group, threadIdx.x, kThreads);
+    combine_and_store(p, it, lds, p.group, threadIdx.x, kThreads, row_mode(p, it.n_live));
 }
 
 // ---------------------------------------------------------------------------------------------------
 // persistent form
 // ---------------------------------------------------------------------------------------------------
-// Workspace: 16 words of header (see decode_list_kernel), then batch * max_chunks entries.
+// Workspace: 16 words of header (see decode_list_kernel), then batch * max_chunks entries, then one arrival
+// counter per (sequence, kv head).
 constexpr int kHeaderWords = 16;
 
 // Ranges of up to kShortTokens tokens ("short") are dealt out one per wave, four to a ticket; the sort keeps
@@ -677,7 +838,7 @@ __device__ __forceinline__ unsigned wave_take_slot(unsigned* counters, int key, 
 constexpr int kListCachedSeqs = 2048;                  // sequences whose ranges the list kernel keeps in LDS
 
 __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsigned* __restrict__ header,
-                                                           WorkEntry* __restrict__ entries)
+                                                           WorkEntry* __restrict__ entries, unsigned* __restrict__ arrivals)
 {
     __shared__ unsigned hist[kSortBins + 1];               // last counter: empty entries
     __shared__ int sh_b[kListCachedSeqs], sh_e[kListCachedSeqs];
@@ -703,7 +864,9 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         if (cached) { b = sh_b[seq]; en = sh_e[seq]; }
         else seq_range(p, seq, b, en);
         chunk_range(p, b, en, chunk, cb, ce);
+        return live_chunks(p, b, en);
     };
+    for (int i = threadIdx.x; i < p.batch * p.hkv; i += blockDim.x) arrivals[i] = 0;
     for (int base = 0; base < total; base += blockDim.x) {
         const int e = base + threadIdx.x;
         int seq, chunk, cb = 0, ce = 0;
@@ -742,12 +905,12 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
     __syncthreads();
     for (int base = 0; base < total; base += blockDim.x) {
         const int e = base + threadIdx.x;
-        int seq = 0, chunk = 0, cb = 0, ce = 0;
-        if (e < total) entry_range(e, seq, chunk, cb, ce);
+        int seq = 0, chunk = 0, cb = 0, ce = 0, n_live = 0;
+        if (e < total) n_live = entry_range(e, seq, chunk, cb, ce);
         const bool live = ce > cb;
         const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total,
                                              full_bin, kSortBins);
-        if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, chunk, cb, ce};
+        if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, (int)((unsigned)chunk | ((unsigned)n_live << 16)), cb, ce};
     }
 }
 
@@ -807,7 +970,8 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     // worst that can come of it, never an access outside the table or the output buffers.
     const int cap = p.max_blocks * kBlockSize;
     it.seq = min(max(w.seq, 0), p.batch - 1);
-    it.chunk = min(max(w.chunk, 0), p.max_chunks - 1);
+    it.chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
+    it.n_live = min(max((int)((unsigned)w.chunk >> 16), 1), p.max_chunks);
     it.cb = min(max(w.cb, 0), cap - 1);
     it.ce = min(max(w.ce, it.cb + 1), cap);
     finish_item(it, block_table, p.max_blocks);
@@ -817,16 +981,16 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     return it;
 }
 
-constexpr int kItemWords = 2 + 3 * kWaves;             // what the streaming waves tell the writer about an item
+constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming waves tell the writer about an item
 
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
-    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
+    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ unsigned sh_ticket[3];
-    // by ticket parity: [0] 1 if the workgroup's last, [1] 1 if one item per wave, then (seq, chunk, kvh) of
-    // the item (slot 0) or of each wave's item (seq < 0: the wave had none)
+    // by ticket parity: [0] 1 if the workgroup's last, [1] 1 if one item per wave, then (seq, chunk, kvh,
+    // non-empty chunks of the sequence) of the item (slot 0) or of each wave's item (seq < 0: the wave had none)
     __shared__ int sh_item[2][kItemWords];
     const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by ticket parity
     char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
@@ -837,14 +1001,23 @@ __device__ __forceinline__ void persistent_body(
     const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
 
-    // rows of empty chunks: LSE = -inf (stores only, shared out over the resident workgroups)
+    // rows of empty chunks: LSE = -inf, and the final row of a sequence whose whole range is empty (stores
+    // only, shared out over the resident workgroups); and which sequences this call finishes
     auto store_empty_share = [&] {
         const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
         const unsigned n_empty = min(counts[1], last + 1u);
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
             const WorkEntry w = load_invariant(entries + (last - i));
-            store_empty(p, min(max(w.seq, 0), p.batch - 1), min(max(w.chunk, 0), p.max_chunks - 1), 0, p.hq,
-                        id.lane, kWave);
+            const int chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
+            store_empty(p, min(max(w.seq, 0), p.batch - 1), chunk, 0, p.hq, id.lane, kWave,
+                        p.out_o != nullptr && chunk == 0);
+        }
+        if (p.seq_final) {
+            for (int i = blockIdx.x * kWave + id.lane; i < p.batch; i += gridDim.x * kWave) {
+                int b, e;
+                seq_range(p, i, b, e);
+                p.seq_final[i] = (p.out_o != nullptr && (p.fuse || live_chunks(p, b, e) <= 1)) ? 1 : 0;
+            }
         }
     };
 
@@ -897,17 +1070,37 @@ __device__ __forceinline__ void persistent_body(
             const bool last = si[0] != 0, grouped = si[1] != 0;
             const float* area = reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes);
             Item done;
-            if (!grouped) {
-                done.seq = si[2];
-                done.chunk = si[3];
-                done.kvh = si[4];
-                combine_and_store(p, done, area, p.group, id.lane, kWave);
-            } else {
-                for (int w = 0; w < kWaves; ++w) {
-                    done.seq = si[2 + 3 * w];
-                    done.chunk = si[3 + 3 * w];
-                    done.kvh = si[4 + 3 * w];
-                    if (done.seq >= 0) combine_and_store(p, done, area, p.group, id.lane, kWave, w, w + 1);
+            bool shared = false;
+            const int n_done = grouped ? kWaves : 1;
+            for (int w = 0; w < n_done; ++w) {
+                done.seq = uniform(si[2 + 4 * w]);
+                done.chunk = uniform(si[3 + 4 * w]);
+                done.kvh = uniform(si[4 + 4 * w]);
+                if (done.seq < 0) continue;
+                const int mode = row_mode(p, uniform(si[5 + 4 * w]));
+                shared |= mode == kRowShared;
+                if (grouped) combine_and_store(p, done, area, p.group, id.lane, kWave, mode, w, w + 1);
+                else combine_and_store(p, done, area, p.group, id.lane, kWave, mode);
+            }
+            if (shared) {
+                // The fused form.  The rows just stored (at device scope) have left this wave for good once
+                // its vector-memory counter is back to zero; only then does the item count as arrived.
+                // Whoever brings a (sequence, kv head)'s count to the number of its non-empty chunks finds
+                // every one of those rows in place, merges them and puts the counter back to zero.
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                OMNI_WAIT_VMCNT(0);
+                for (int w = 0; w < n_done; ++w) {
+                    const int seq = uniform(si[2 + 4 * w]), kvh = uniform(si[4 + 4 * w]), n_live = uniform(si[5 + 4 * w]);
+                    if (seq < 0 || row_mode(p, n_live) != kRowShared) continue;
+                    unsigned* counter = arrivals + (long long)seq * p.hkv + kvh;
+                    unsigned before = 0;
+                    if (id.lane == 0) before = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    before = (unsigned)uniform((int)before);
+                    if (before + 1u == (unsigned)n_live) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                        merge_chunks_and_store(p, seq, kvh, n_live, p.group, id.lane, kWave);
+                        if (id.lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
             if (last) break;
@@ -1020,9 +1213,10 @@ __device__ __forceinline__ void persistent_body(
                 si[0] = has_next ? 0 : 1;
                 si[1] = grouped ? 1 : 0;
             }
-            si[2 + 3 * id.wave] = streamed ? it.seq : -1;
-            si[3 + 3 * id.wave] = it.chunk;
-            si[4 + 3 * id.wave] = it.kvh;
+            si[2 + 4 * id.wave] = streamed ? it.seq : -1;
+            si[3 + 4 * id.wave] = it.chunk;
+            si[4 + 4 * id.wave] = it.kvh;
+            si[5 + 4 * id.wave] = it.n_live;
         }
         lds_barrier();
         if (!has_next) break;
@@ -1039,9 +1233,9 @@ __device__ __forceinline__ void persistent_body(
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
 __global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
-    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries)
+    const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
-    persistent_body(p, block_table, header, counts, entries);
+    persistent_body(p, block_table, header, counts, entries, arrivals);
     if (threadIdx.x == 0) {
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
@@ -1068,9 +1262,10 @@ bool decode_mfma_supports(const DecodeParams& p, bool bf16)
            (long long)p.batch * p.max_chunks * p.hkv <= 0x7fffffffLL;
 }
 
-size_t decode_workspace_bytes(long long batch, long long max_chunks)
+size_t decode_workspace_bytes(long long batch, long long max_chunks, long long hkv)
 {
-    return (size_t)kHeaderWords * sizeof(unsigned) + (size_t)(batch * max_chunks) * sizeof(WorkEntry);
+    const size_t counters = ((size_t)(batch * hkv) * sizeof(unsigned) + 15) / 16 * 16;
+    return (size_t)kHeaderWords * sizeof(unsigned) + (size_t)(batch * max_chunks) * sizeof(WorkEntry) + counters;
 }
 
 // Host-side views of the work-list logic, for tests: the sort bin of a range, and which list item every
@@ -1099,7 +1294,8 @@ hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_
 {
     unsigned* header = static_cast<unsigned*>(workspace);
     WorkEntry* entries = reinterpret_cast<WorkEntry*>(header + kHeaderWords);
-    hipLaunchKernelGGL(decode_list_kernel, dim3(1), dim3(1024), 0, s, p, header, entries);
+    unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
+    hipLaunchKernelGGL(decode_list_kernel, dim3(1), dim3(1024), 0, s, p, header, entries, arrivals);
     return hipGetLastError();
 }
 
@@ -1166,8 +1362,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     // of the launch than their overlap gains in between (measured on every configuration).
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
+    unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
     hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p,
-                       p.block_table, header, header + 1, entries);
+                       p.block_table, header, header + 1, entries, arrivals);
     return hipGetLastError();
 }
 

@@ -58,6 +58,9 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
     int b, e, cb, ce;
     seq_range(p, seq, b, e);
     chunk_range(p, b, e, chunk, cb, ce);
+    // a sequence with at most one non-empty chunk (chunk 0) gets its final row from this kernel
+    const bool seq_direct = p.out_o != nullptr && live_chunks(p, b, e) <= 1;
+    if (p.seq_final && head == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
 
     float q[E];
     RowVec<T, E>::load(p.q, ((long long)seq * p.hq + head) * D + sub * E, q);
@@ -103,7 +106,8 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
 #pragma unroll
     for (int g = 0; g < kGroups; ++g) mm = fmaxf(mm, sh_m[g]);
     const long long prow = ((long long)seq * p.max_chunks + chunk) * p.hq + head;
-    const bool final_row = (p.out_o != nullptr) && (p.max_chunks == 1);
+    const bool final_row = seq_direct && chunk == 0;
+    const bool partial_row = !seq_direct || p.max_chunks == 1;     // a one-slot call keeps the partial as well
     const long long orow = (long long)seq * p.hq + head;
     float o = 0.f, lse = -INFINITY;
     if (mm != -INFINITY) {
@@ -116,9 +120,9 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
         }
         o = oo / ll;
         lse = mm + logf(ll);
-        if (p.part_o) p.part_o[prow * D + dim] = o;
+        if (p.part_o && partial_row) p.part_o[prow * D + dim] = o;
     }
-    if (p.part_lse && dim == 0) p.part_lse[prow] = lse;
+    if (p.part_lse && dim == 0) p.part_lse[prow] = partial_row ? lse : -INFINITY;
     if (final_row) {
         if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow * D + dim] = f32_to_bf16(o);
         else static_cast<float*>(p.out_o)[orow * D + dim] = o;

@@ -13,12 +13,6 @@
 namespace omni {
 namespace {
 
-__device__ __forceinline__ void src_rows(const omni_partial_src& s, int seq, int& r0, int& r1)
-{
-    if (s.row_offsets) { r0 = s.row_offsets[seq]; r1 = s.row_offsets[seq + 1]; }
-    else { r0 = seq * s.dense_rows_per_seq; r1 = r0 + s.dense_rows_per_seq; }
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
 {
@@ -28,6 +22,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     const int quad = threadIdx.x % kLanesPerRow;
     if (row >= (long long)p.batch * p.hq) return;
     const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
+    if (p.skip && p.skip[seq] != 0) return;                // the decode call already wrote this sequence's final row
 
     // Rows are visited eight at a time so that eight independent loads are in flight per lane: the kernel
     // is a handful of dependent memory round trips, not a bandwidth problem.

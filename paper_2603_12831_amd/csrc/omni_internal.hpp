@@ -24,14 +24,25 @@ struct DecodeParams {
     const int* block_table;
     const int* ctx_begin;          // may be null
     const int* ctx_end;
-    int chunk_tokens;              // > 0 here: "one chunk" is expressed as INT_MAX/2 rounded to pages
+    int chunk_tokens;              // > 0 here: "one chunk" is expressed as the whole table width, max_blocks * 16
     int max_chunks;
-    float* part_o;                 // may be null
+    float* part_o;                 // may be null (only when every row is written as a final row)
     float* part_lse;               // may be null
-    void* out_o;                   // may be null; only honoured when max_chunks == 1
+    void* out_o;                   // may be null; final rows of the sequences that this call can finish
     int out_bf16;
     float* out_lse;                // may be null
+    int* seq_final;                // may be null; [batch] 1 = the call wrote the sequence's final row
+    int fuse;                      // 1 = every sequence is finished in the attention launch (persistent form)
+    int n_ext;                     // fused form: sources of rows computed elsewhere, folded into the final rows
+    omni_partial_src ext[3];
 };
+
+// Rows of sequence `seq` in a source of partial rows.
+__device__ __forceinline__ void src_rows(const omni_partial_src& s, int seq, int& r0, int& r1)
+{
+    if (s.row_offsets) { r0 = s.row_offsets[seq]; r1 = s.row_offsets[seq + 1]; }
+    else { r0 = seq * s.dense_rows_per_seq; r1 = r0 + s.dense_rows_per_seq; }
+}
 
 // Flattened, validated form of omni_kv_cache.
 struct KvParams {
@@ -55,6 +66,7 @@ struct MergeParams {
     int n_srcs, batch, hq, d, out_bf16;
     void* out_o;
     float* out_lse;
+    const int* skip;               // may be null; [batch] non-zero = leave the sequence's rows alone
 };
 
 // ---- device helpers -------------------------------------------------------
@@ -90,11 +102,19 @@ __device__ __forceinline__ void chunk_range(const DecodeParams& p, int b, int e,
     ce = hi < e ? (int)hi : e;
 }
 
+// Number of non-empty chunks of a sequence whose clamped range is [b, e): chunks 0 .. n-1 are the live ones.
+__device__ __forceinline__ int live_chunks(const DecodeParams& p, int b, int e)
+{
+    if (e <= b) return 0;
+    const long long n = ((long long)(e - b) + p.chunk_tokens - 1) / p.chunk_tokens;
+    return n < p.max_chunks ? (int)n : p.max_chunks;
+}
+
 // ---- launchers (each defined beside its kernel) ---------------------------
 hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s);
 hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s);
-size_t decode_workspace_bytes(long long batch, long long max_chunks);
+size_t decode_workspace_bytes(long long batch, long long max_chunks, long long hkv);
 bool decode_mfma_supports(const DecodeParams& p, bool bf16);
 int decode_list_sort_bin(int tokens, int chunk_tokens);
 unsigned decode_ticket_map(unsigned n_entries, unsigned n_long_entries, unsigned hkv, unsigned n_workgroups,

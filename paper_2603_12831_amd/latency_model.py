@@ -95,7 +95,7 @@ def measure(samples, reps: int = 7, hq: int = 32, hkv: int = 8, chunk_tokens: in
         part_lse = torch.empty((B, max_chunks, hq), dtype=torch.float32, device=dev)
         out_o = torch.empty((B, hq, d), dtype=torch.bfloat16, device=dev)
         out_lse = torch.empty((B, hq), dtype=torch.float32, device=dev)
-        ws = torch.empty(binding.omni_decode_workspace_bytes(B, max_chunks), dtype=torch.uint8, device=dev)
+        ws = torch.empty(binding.omni_decode_workspace_bytes(B, max_chunks, hkv), dtype=torch.uint8, device=dev)
 
         def once():
             binding.omni_paged_decode_attn(q, k_pool, v_pool, bt, None, end, sm_scale=d ** -0.5,
@@ -116,7 +116,8 @@ def measure(samples, reps: int = 7, hq: int = 32, hkv: int = 8, chunk_tokens: in
     return np.array(times)
 
 
-def profile_and_fit(n_samples: int = 60, seed: int = 0, train_frac: float = 0.7, **kw) -> Dict:
+def profile_and_fit(n_samples: int = 60, seed: int = 0, train_frac: float = 0.7, keep_samples: bool = False,
+                    **kw) -> Dict:
     samples = sample_batches(seed, n_samples)
     t = measure(samples, **kw)
     c = np.array([int(s.sum()) for s in samples], dtype=np.float64)
@@ -124,7 +125,8 @@ def profile_and_fit(n_samples: int = 60, seed: int = 0, train_frac: float = 0.7,
     n_train = max(3, int(round(train_frac * n_samples)))
     model = fit(c[:n_train], g[:n_train], t[:n_train])
     held = slice(n_train, None) if n_train < n_samples else slice(0, None)
-    return {"model_ms": model, "train_samples": n_train, "test_samples": int(len(c[held])),
+    extra = {"samples": {"c_da": c.tolist(), "g": g.tolist(), "ms": t.tolist()}} if keep_samples else {}
+    return {**extra, "model_ms": model, "train_samples": n_train, "test_samples": int(len(c[held])),
             "accuracy_train": accuracy(predict(model, c[:n_train], g[:n_train]), t[:n_train]),
             "accuracy_test": accuracy(predict(model, c[held], g[held]), t[held]),
             "ns_per_context_token": model["a"] * 1e6, "us_per_request": model["h"] * 1e3,
@@ -138,8 +140,9 @@ def main() -> int:
     ap.add_argument("--samples", type=int, default=60)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--out", default=None)
+    ap.add_argument("--keep-samples", action="store_true", help="include the measured (c_DA, g, ms) samples")
     args = ap.parse_args()
-    res = profile_and_fit(args.samples, args.seed)
+    res = profile_and_fit(args.samples, args.seed, keep_samples=args.keep_samples)
     line = json.dumps(res)
     print(line)
     if args.out:

@@ -24,7 +24,19 @@ class DeviceWorkload:
 
     def __init__(self, w: Workload, device="cuda:0", out_dtype: Optional[str] = None,
                  ext_o: Optional[np.ndarray] = None, ext_lse: Optional[np.ndarray] = None,
-                 ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1, workspace: bool = True):
+                 ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1, workspace: bool = True,
+                 mode: str = "merge"):
+        """mode: how the final rows come about.
+        "merge"  every chunk writes a partial row, omni_merge_partials makes the final rows (a single
+                 one-chunk call with nothing else to merge writes them itself);
+        "final"  the decode call also writes the final rows of the sequences it can finish (one non-empty
+                 chunk), the masked merge does the others;
+        "fused"  the decode call finishes every sequence (in-launch merge, external rows folded in)."""
+        if mode not in ("merge", "final", "fused"):
+            raise ValueError("unknown mode %r" % mode)
+        if mode != "merge" and len(w.calls) != 1:
+            raise ValueError("mode %r needs a workload with one decode call" % mode)
+        self.mode = mode
         self.w = w
         self.device = torch.device(device)
         k_pool, v_pool, table = w.device_views()
@@ -42,8 +54,8 @@ class DeviceWorkload:
                 chunk_tokens=c.chunk_tokens, max_chunks=c.max_chunks,
                 part_o=torch.empty((B, c.max_chunks, Hq, D), dtype=torch.float32, device=self.device),
                 part_lse=torch.empty((B, c.max_chunks, Hq), dtype=torch.float32, device=self.device),
-                workspace=torch.zeros(binding.omni_decode_workspace_bytes(B, c.max_chunks), dtype=torch.uint8,
-                                      device=self.device) if workspace else None))
+                workspace=torch.zeros(binding.omni_decode_workspace_bytes(B, c.max_chunks, w.num_kv_heads),
+                                      dtype=torch.uint8, device=self.device) if workspace else None))
         self.ext = None
         if ext_o is not None:
             self.ext = (torch.from_numpy(np.ascontiguousarray(ext_o, dtype=np.float32)).to(self.device),
@@ -53,8 +65,11 @@ class DeviceWorkload:
         self.out_o = torch.empty((B, Hq, D), dtype=torch.bfloat16 if od == "bf16" else torch.float32,
                                  device=self.device)
         self.out_lse = torch.empty((B, Hq), dtype=torch.float32, device=self.device)
+        self.seq_final = torch.zeros(B, dtype=torch.int32, device=self.device)
         # a single one-chunk call with nothing else to merge writes the final rows itself
         self.direct = len(self.calls) == 1 and self.calls[0]["max_chunks"] == 1 and self.ext is None
+        if self.direct:
+            self.mode = "merge"
 
     def poison_outputs(self):
         """Fill every output with NaN so that stale data cannot pass a check."""
@@ -65,12 +80,15 @@ class DeviceWorkload:
         self.out_lse.fill_(float("nan"))
 
     def decode_args(self, c, kernel: int, pool: int, planned: bool):
+        final = self.direct or self.mode != "merge"
         return binding.make_decode_args(
             self.q, self.k_pools[pool], self.v_pools[pool], self.block_table, c["begin"], c["end"],
             sm_scale=self.w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
             part_o=None if self.direct else c["part_o"], part_lse=None if self.direct else c["part_lse"],
-            out_o=self.out_o if self.direct else None, out_lse=self.out_lse if self.direct else None,
-            kernel=kernel, workspace=c["workspace"], workspace_planned=planned)
+            out_o=self.out_o if final else None, out_lse=self.out_lse if final else None,
+            kernel=kernel, workspace=c["workspace"], workspace_planned=planned,
+            seq_final=self.seq_final if self.mode != "merge" else None, fuse_merge=self.mode == "fused",
+            ext_srcs=[self.ext] if (self.mode == "fused" and self.ext is not None) else None)
 
     def plan(self, stream=None):
         """Build the work list of every decode call once (it can then serve many attention passes)."""
@@ -80,18 +98,8 @@ class DeviceWorkload:
 
     def run_attention(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None,
                       planned: bool = False):
-        w = self.w
-        if planned:
-            for c in self.calls:
-                binding.omni_paged_decode_attn_raw(self.decode_args(c, kernel, pool, True), stream)
-            return
         for c in self.calls:
-            binding.omni_paged_decode_attn(
-                self.q, self.k_pools[pool], self.v_pools[pool], self.block_table, c["begin"], c["end"],
-                sm_scale=w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
-                part_o=None if self.direct else c["part_o"], part_lse=None if self.direct else c["part_lse"],
-                out_o=self.out_o if self.direct else None, out_lse=self.out_lse if self.direct else None,
-                kernel=kernel, workspace=c["workspace"], stream=stream)
+            binding.omni_paged_decode_attn_raw(self.decode_args(c, kernel, pool, planned), stream)
 
     def merge_sources(self) -> List:
         srcs = [self.ext] if self.ext is not None else []
@@ -99,11 +107,15 @@ class DeviceWorkload:
         return srcs
 
     def run_merge(self, stream=None):
-        if self.direct:
+        if self.direct or self.mode == "fused":
             return
         w = self.w
-        binding.omni_merge_partials(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(), self.out_o,
-                                    self.out_lse, stream=stream)
+        if self.mode == "final":
+            binding.omni_merge_partials_masked(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(),
+                                               self.seq_final, self.out_o, self.out_lse, stream=stream)
+        else:
+            binding.omni_merge_partials(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(), self.out_o,
+                                        self.out_lse, stream=stream)
 
     def run(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
         """One pass of the whole hot path: every decode call, then the merge."""

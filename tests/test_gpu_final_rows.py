@@ -1,0 +1,218 @@
+"""GPU parity of the decode call's final rows: sequences the call can finish itself (one non-empty chunk)
+written directly with the others left to the masked merge, and the fused form in which the attention
+launch finishes every sequence (partials of several chunks merged by the workgroup that comes last, rows
+computed elsewhere folded in).  Everything against the CPU fp64 oracle, and the routes against each other."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle
+from paper_2603_12831_amd import binding, workloads as wl
+from paper_2603_12831_amd.runner import DeviceWorkload
+from test_gpu_parity import (BENCH_FORM, KERNELS, THREADS, TOL, check, expected_full,
+                             ext_partials_from_oracle)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m gpu on an MI355X box)")
+    binding.load_library()
+
+
+def run_mode(w, mode, kernel=BENCH_FORM, out_dtype="f32", ext=None, passes=1):
+    ext = ext or (None, None, None)
+    dw = DeviceWorkload(w, out_dtype=out_dtype, ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2],
+                        workspace=kernel[1], mode=mode)
+    for _ in range(passes):
+        dw.poison_outputs()
+        dw.seq_final.fill_(-7)
+        dw.run(kernel=kernel[0])
+    o, l = dw.results()
+    if kernel[1]:
+        assert dw.abandoned_waves() == 0
+    return o, l, dw
+
+
+def live_chunk_count(w):
+    c = w.calls[0]
+    tok = np.maximum(c.ctx_end.astype(np.int64) - c.ctx_begin, 0)
+    ct = c.chunk_tokens if c.chunk_tokens else 1 << 30
+    return np.minimum((tok + ct - 1) // ct, c.max_chunks)
+
+
+def mixed_batch(seed=71, dtype="bf16", hq=8, hkv=2, d=128, chunk=128):
+    """Ranges of zero, one and several chunks, some starting past token 0."""
+    lengths = np.array([1, 40, 128, 129, 300, 127, 0, 513, 64, 1000, 128, 5, 260, 90, 0, 384])
+    begin = np.array([0, 3, 0, 0, 17, 0, 0, 1, 60, 0, 1, 0, 4, 0, 0, 0])
+    w = wl.make_generic(seed, np.maximum(lengths + begin, 1), hq, hkv, d, dtype=dtype, chunk_tokens=chunk,
+                        ctx_begin=begin, pool_factor=1.3)
+    w.calls[0].ctx_end = (lengths + begin).astype(np.int32)
+    w.calls[0].max_chunks = int((int(lengths.max()) + chunk - 1) // chunk)
+    return w
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_final_rows_of_single_chunk_sequences(kernel, out_dtype):
+    """Mixed batch: the call writes the final rows of the sequences with at most one non-empty chunk and
+    says so in seq_final; those rows equal the merged route bit for bit and their partial rows are never
+    written; the masked merge completes the batch."""
+    w = mixed_batch()
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    o_m, l_m, _ = run_mode(w, "merge", kernel, out_dtype)
+    dw = DeviceWorkload(w, out_dtype=out_dtype, workspace=kernel[1], mode="final")
+    dw.poison_outputs()
+    dw.seq_final.fill_(-7)
+    dw.run_attention(kernel=kernel[0])
+    torch.cuda.synchronize()
+    single = live_chunk_count(w) <= 1
+    assert np.array_equal(dw.seq_final.cpu().numpy(), single.astype(np.int32))
+    o_a = dw.out_o.float().cpu().numpy().astype(np.float64)
+    l_a = dw.out_lse.cpu().numpy().astype(np.float64)
+    # finished rows are there already, bit-identical to the merged route; the others untouched (NaN)
+    assert np.array_equal(o_a[single], o_m[single]) and np.array_equal(l_a[single], l_m[single])
+    assert np.all(np.isnan(o_a[~single])) and np.all(np.isnan(l_a[~single]))
+    po = dw.calls[0]["part_o"].cpu().numpy()
+    pl = dw.calls[0]["part_lse"].cpu().numpy()
+    assert np.all(np.isnan(po[single])), "a finished sequence wrote a partial row"
+    assert np.all(pl[single] == -np.inf)
+    dw.run_merge()
+    o_f, l_f = dw.results()
+    assert np.array_equal(o_f, o_m) and np.array_equal(l_f, l_m)
+    tol = TOL["bf16"] + (float(np.max(np.abs(exp[0]))) * 2.0 ** -9 if out_dtype == "bf16" else 0.0)
+    check(o_f, l_f, exp[0], exp[1], tol, "final rows + masked merge")
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (8, 2, 64)), ("bf16", (8, 8, 64)), ("f32", (4, 4, 128))])
+def test_final_rows_vector_kernel(dtype, shape):
+    hq, hkv, d = shape
+    w = mixed_batch(seed=72, dtype=dtype, hq=hq, hkv=hkv, d=d, chunk=64)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    o_m, l_m, _ = run_mode(w, "merge", (binding.OMNI_KERNEL_VECTOR, False))
+    o_f, l_f, dw = run_mode(w, "final", (binding.OMNI_KERNEL_VECTOR, False))
+    assert np.array_equal(dw.seq_final.cpu().numpy(), (live_chunk_count(w) <= 1).astype(np.int32))
+    assert np.array_equal(o_f, o_m) and np.array_equal(l_f, l_m)
+    check(o_f, l_f, exp[0], exp[1], TOL[dtype], "vector kernel final rows")
+
+
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(8, 2, 128), (16, 1, 160), (6, 3, 64), (8, 8, 256)])
+def test_fused_form_finishes_every_sequence(out_dtype, shape):
+    """The attention launch alone: sequences of zero, one and several chunks, run three times on the same
+    buffers and work list (the arrival counters must come back to zero), equal to the oracle and, to
+    rounding of the different merge order, to the two-launch route."""
+    hq, hkv, chunk = shape
+    w = mixed_batch(seed=73 + hq, hq=hq, hkv=hkv, chunk=chunk)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    tol = TOL["bf16"] + (float(np.max(np.abs(exp[0]))) * 2.0 ** -9 if out_dtype == "bf16" else 0.0)
+    o_m, l_m, _ = run_mode(w, "merge", out_dtype=out_dtype)
+    o_f, l_f, dw = run_mode(w, "fused", out_dtype=out_dtype, passes=3)
+    assert np.all(dw.seq_final.cpu().numpy() == 1)
+    check(o_f, l_f, exp[0], exp[1], tol, "fused form")
+    single = live_chunk_count(w) <= 1
+    assert np.array_equal(o_f[single], o_m[single]) and np.array_equal(l_f[single], l_m[single])
+    # a planned list reused by the fused form
+    dw.plan()
+    for _ in range(2):
+        dw.poison_outputs()
+        dw.run_attention(planned=True)
+        o_p, l_p = dw.results()
+        assert np.array_equal(o_p, o_f) and np.array_equal(l_p, l_f)
+
+
+def test_fused_form_many_chunks_is_deterministic():
+    """Rows of up to 40 chunks with many more items than workgroups: the merge must find every partial row
+    of the launch in place whichever workgroup comes last; repeated runs are bit-identical."""
+    rng = np.random.default_rng(74)
+    lengths = rng.integers(1, 2600, size=300)
+    lengths[::7] = rng.integers(1, 60, size=len(lengths[::7]))
+    w = wl.make_generic(74, lengths, 16, 4, 128, dtype="bf16", chunk_tokens=64)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    o1, l1, dw = run_mode(w, "fused")
+    check(o1, l1, exp[0], exp[1], TOL["bf16"], "fused, many chunks")
+    for _ in range(4):
+        dw.poison_outputs()
+        dw.run()
+        o2, l2 = dw.results()
+        assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    assert dw.abandoned_waves() == 0
+
+
+def test_fused_form_folds_rows_computed_elsewhere():
+    """Hybrid batch: resident tails on the GPU, prefix partials from the oracle (fp32) as an external
+    source folded in by the attention launch; also with the tails cut into chunks, and with sequences
+    whose resident range is empty (their rows come from the external source alone)."""
+    w = wl.make_cfg4(n_ls=5, n_be=20, ls_lo=20, ls_hi=600, be_lo=300, be_hi=900, tail_lo=5, tail_hi=200)
+    ext = ext_partials_from_oracle(w)
+    exp = expected_full(w)
+    o_m, l_m, _ = run_mode(w, "merge", ext=ext)
+    check(o_m, l_m, exp[0], exp[1], TOL["bf16"], "two launches")
+    o_f, l_f, _ = run_mode(w, "fused", ext=ext, passes=2)
+    check(o_f, l_f, exp[0], exp[1], TOL["bf16"], "fused hybrid")
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 64, 12
+    o_c, l_c, _ = run_mode(w, "fused", ext=ext, passes=2)
+    check(o_c, l_c, exp[0], exp[1], TOL["bf16"], "fused hybrid, chunked tails")
+    # two best-effort rows without resident tokens, one latency-sensitive row without any context at all
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 0, 1
+    n_ls = w.meta["n_ls"]
+    end = w.calls[0].ctx_end.copy()
+    for i in (n_ls + 1, n_ls + 4):
+        end[i] = w.calls[0].ctx_begin[i]
+    end[2] = 0
+    w.calls[0].ctx_end = end
+    exp2 = expected_full(w, begin=np.zeros_like(end), end=end)
+    o_e, l_e, _ = run_mode(w, "fused", ext=ext)
+    assert np.all(o_e[2] == 0) and np.all(l_e[2] == -np.inf)
+    check(o_e, l_e, exp2[0], exp2[1], TOL["bf16"], "fused hybrid, empty resident ranges")
+
+
+def test_fused_form_needs_the_persistent_kernel():
+    w = mixed_batch(seed=75)
+    dw = DeviceWorkload(w, out_dtype="f32", workspace=False, mode="fused")
+    args = dw.decode_args(dw.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_UNSUPPORTED
+    wf = mixed_batch(seed=75, dtype="f32", d=64)
+    dwf = DeviceWorkload(wf, out_dtype="f32", workspace=True, mode="fused")
+    args = dwf.decode_args(dwf.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_UNSUPPORTED
+    # final rows for part of the batch without a seq_final array: refused
+    dw2 = DeviceWorkload(w, out_dtype="f32", mode="final")
+    args = dw2.decode_args(dw2.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    args.seq_final = None
+    assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_NULL
+
+
+def test_fused_step_in_a_graph_replays_exactly():
+    w = wl.make_cfg3(batch=40, median=600, lo=1, hi=4000, chunk_tokens=512)
+    exp = expected_full(w)
+    o_e, l_e, dw = run_mode(w, "fused")
+    check(o_e, l_e, exp[0], exp[1], TOL["bf16"], "fused eager")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dw.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dw.run()
+    for replay in range(4):
+        dw.poison_outputs()
+        torch.cuda.synchronize()
+        graph.replay()
+        o, l = dw.results()
+        assert np.array_equal(o, o_e) and np.array_equal(l, l_e), "replay %d differs" % replay
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_full_size_fused(name):
+    """The full-size configurations through the fused form (what bench.py times)."""
+    w = wl.MAKERS[name](workers=THREADS)
+    ext = ext_partials_from_oracle(w) if w.ext_ranges is not None else None
+    o, l, dw = run_mode(w, "fused", ext=ext, passes=2)
+    exp = expected_full(w)
+    eo, el = check(o, l, exp[0], exp[1], 2e-3, name + " fused")
+    print("%s fused: max abs err O %.3g LSE %.3g" % (name, eo, el))

@@ -569,14 +569,14 @@ def test_full_cfg4():
     print("cfg4 max abs err O %.3g LSE %.3g" % (eo, el))
 
 
-def test_full_cfg5_sampled_sequences():
+def test_full_cfg5_all_sequences():
+    """Every head of all 32 sequences at the full size (32 chunks of 1024 tokens merged per row)."""
     w = wl.make_cfg5(workers=THREADS)
     dw = DeviceWorkload(w, out_dtype="f32")
     dw.poison_outputs()
     dw.run()
     got_o, got_l = dw.results()
-    assert np.all(np.isfinite(got_o)) and np.all(np.isfinite(got_l))
-    seqs = [0, 7, 13, 31]                                            # every head of four sequences
-    exp_o, exp_l = expected_full(w, seqs=seqs)
-    eo, el = check(got_o[seqs], got_l[seqs], exp_o, exp_l, 2e-3, "cfg5")
-    print("cfg5 max abs err O %.3g LSE %.3g" % (eo, el))
+    assert dw.abandoned_waves() == 0
+    exp_o, exp_l = expected_full(w)
+    eo, el = check(got_o, got_l, exp_o, exp_l, 2e-3, "cfg5")
+    print("cfg5 max abs err over all %d x %d rows: O %.3g LSE %.3g" % (w.batch, w.num_q_heads, eo, el))

@@ -66,8 +66,9 @@ def test_decode_argument_errors(over, code):
 
 def test_plan_argument_errors_and_workspace_size():
     lib = binding.load_library()
-    assert lib.omni_decode_workspace_bytes(256, 8) >= 16 * 256 * 8
-    assert lib.omni_decode_workspace_bytes(0, 8) == 0 and lib.omni_decode_workspace_bytes(4, -1) == 0
+    assert lib.omni_decode_workspace_bytes(256, 8, 8) >= 16 * 256 * 8 + 4 * 256 * 8
+    assert lib.omni_decode_workspace_bytes(0, 8, 8) == 0 and lib.omni_decode_workspace_bytes(4, -1, 8) == 0
+    assert lib.omni_decode_workspace_bytes(4, 1, 0) == 0
     assert lib.omni_decode_plan(None, None) == binding.OMNI_ERR_NULL
     assert lib.omni_decode_plan(ctypes.byref(_args()), None) == binding.OMNI_ERR_NULL        # no workspace
     assert lib.omni_decode_plan(ctypes.byref(_args(workspace=0x1000, workspace_bytes=8)), None) == binding.OMNI_ERR_SHAPE

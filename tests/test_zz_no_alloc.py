@@ -61,7 +61,7 @@ def test_static_scratch_entry_rejects_what_does_not_fit():
     args = dw.decode_args(dw.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
     # claim a chunk stride whose list cannot fit the scratch: rejected on the host, nothing launched
     args.max_chunks = 65535
-    assert binding.omni_decode_workspace_bytes(2, 65535) > binding.OMNI_STATIC_SCRATCH_BYTES
+    assert binding.omni_decode_workspace_bytes(2, 65535, 2) > binding.OMNI_STATIC_SCRATCH_BYTES
     assert binding.omni_paged_decode_attn_static(args, check=False) == binding.OMNI_ERR_TOO_LARGE
     assert "scratch" in binding.omni_status_string(binding.OMNI_ERR_TOO_LARGE)
     assert binding.load_library().omni_paged_decode_attn_static(None, None) == binding.OMNI_ERR_NULL
