@@ -505,54 +505,97 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
-// Folds the rows that the sources of rows computed elsewhere hold for sequence `seq`, query head `head`
-// (dims d .. d+3) into (o, lse), which is this launch's own contribution (lse = -inf and o = 0: none).
-// The merge rule is the disjoint-union identity of Eq. 1 (as in the merge kernel: maximum first, then the
-// weights), rows eight at a time so that eight independent loads are in flight.
-__device__ __forceinline__ void fold_ext_rows(const DecodeParams& p, int seq, int head, int d, f32x4& o, float& lse)
+// Running merge of partial rows for four dims of one head, by the disjoint-union identity of Eq. 1 in its
+// incremental form (natural-log units): acc = sum w_r O_r and wsum = sum w_r with w_r = exp(LSE_r - m).
+struct RowAcc {
+    float m, wsum;
+    f32x4 acc;
+    __device__ __forceinline__ void start(f32x4 o, float lse)   // a normalised row (o, lse); lse = -inf: nothing yet
+    {
+        m = lse;
+        wsum = lse == -INFINITY ? 0.f : 1.f;
+        acc = lse == -INFINITY ? f32x4{0.f, 0.f, 0.f, 0.f} : o;
+    }
+    __device__ __forceinline__ void finish(f32x4& o, float& lse) const
+    {
+        if (m == -INFINITY) { o = f32x4{0.f, 0.f, 0.f, 0.f}; lse = -INFINITY; return; }
+        o = acc * (1.f / wsum);
+        lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+    }
+};
+
+constexpr int kMergeLanes = 2;     // (head, four dims) positions a lane merges side by side
+constexpr int kMergeTile = 8;      // rows per round trip
+
+// Adds rows 0 .. n-1 (n <= kMergeTile) of some source to the kMergeLanes running merges of a lane.  All
+// LSE values and all O pieces of the tile are requested before anything is used: one memory round trip per
+// tile, whatever the weights turn out to be (the writer wave's merges are chains of such trips, and their
+// number is what they cost).  A row of weight zero (LSE = -inf) is fetched like the others but never enters
+// the sums, so whatever its O holds (it may never have been written) does no harm.
+template <class LseAt, class OAt>
+__device__ __forceinline__ void merge_tile(RowAcc (&a)[kMergeLanes], const bool (&on)[kMergeLanes], int n,
+                                           LseAt&& lse_at, OAt&& o_at)
 {
-    constexpr int kBatch = 8;
-    float m = lse;
-    for (int s = 0; s < p.n_ext; ++s) {
-        int r0, r1;
-        src_rows(p.ext[s], seq, r0, r1);
-        const float* l = p.ext[s].lse + head;
-        for (int r = r0; r < r1; r += kBatch) {
-            float v[kBatch];
+    float l[kMergeLanes][kMergeTile];
+    f32x4 x[kMergeLanes][kMergeTile];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) v[u] = (r + u < r1) ? l[(long long)(r + u) * p.hq] : -INFINITY;
+    for (int k = 0; k < kMergeLanes; ++k)
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) m = fmaxf(m, v[u]);
+        for (int u = 0; u < kMergeTile; ++u) l[k][u] = (on[k] && u < n) ? lse_at(k, u) : -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kMergeLanes; ++k)
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) x[k][u] = (on[k] && u < n) ? o_at(k, u) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < kMergeLanes; ++k) {
+        float m_new = a[k].m;
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) m_new = fmaxf(m_new, l[k][u]);
+        if (m_new == -INFINITY) continue;
+        const float keep = a[k].m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((a[k].m - m_new) * kLog2e);
+        a[k].acc *= keep;
+        a[k].wsum *= keep;
+        a[k].m = m_new;
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) {
+            const bool live = l[k][u] != -INFINITY;
+            const float w = live ? __builtin_amdgcn_exp2f((l[k][u] - m_new) * kLog2e) : 0.f;
+            a[k].wsum += w;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) a[k].acc[c] += live ? w * x[k][u][c] : 0.f;
         }
     }
-    if (m == -INFINITY) return;                                    // no weight anywhere: O = 0, LSE = -inf
-    float wsum = (lse == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((lse - m) * kLog2e);
-    f32x4 acc = o * wsum;
-    for (int s = 0; s < p.n_ext; ++s) {
-        int r0, r1;
-        src_rows(p.ext[s], seq, r0, r1);
-        const float* l = p.ext[s].lse + head;
-        const float* orow = p.ext[s].o + (long long)head * kD + d;
-        for (int r = r0; r < r1; r += kBatch) {
-            float w[kBatch];
-            f32x4 x[kBatch];
+}
+
+// Rows [r0, r1) of the sources of rows computed elsewhere (r0 / r1 per source: the rows of one sequence)
+// into the running merges of positions (head[k], dims d[k] .. d[k]+3).
+__device__ __forceinline__ void fold_ext_rows(const DecodeParams& p, const int (&r0)[3], const int (&r1)[3],
+                                              RowAcc (&a)[kMergeLanes], const bool (&on)[kMergeLanes],
+                                              const int (&head)[kMergeLanes], const int (&d)[kMergeLanes])
+{
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const float v = (r + u < r1) ? l[(long long)(r + u) * p.hq] : -INFINITY;
-                w[u] = (v == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((v - m) * kLog2e);
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {                     // a row without weight is not read at all
-                x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (w[u] != 0.f) x[u] = *reinterpret_cast<const f32x4*>(orow + (long long)(r + u) * p.hq * kD);
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) { wsum += w[u]; acc += w[u] * x[u]; }
+    for (int s = 0; s < 3; ++s) {
+        if (s >= p.n_ext) break;
+        const float* lse = p.ext[s].lse;
+        const float* orow = p.ext[s].o;
+        for (int r = r0[s]; r < r1[s]; r += kMergeTile) {
+            merge_tile(a, on, min(kMergeTile, r1[s] - r),
+                       [&](int k, int u) { return lse[(long long)(r + u) * p.hq + head[k]]; },
+                       [&](int k, int u) {
+                           return *reinterpret_cast<const f32x4*>(orow + ((long long)(r + u) * p.hq + head[k]) * kD + d[k]);
+                       });
         }
     }
-    const float inv = 1.f / wsum;
-    o = acc * inv;
-    lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+}
+
+// rows of sequence `seq` in every source of rows computed elsewhere (wave-uniform)
+__device__ __forceinline__ void ext_row_ranges(const DecodeParams& p, int seq, int (&r0)[3], int (&r1)[3])
+{
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        r0[s] = r1[s] = 0;
+        if (s < p.n_ext) src_rows(p.ext[s], seq, r0[s], r1[s]);
+    }
 }
 
 // four dims of a final row (row = sequence * Hq + head)
@@ -605,91 +648,89 @@ __device__ __forceinline__ f32x4 load_shared4(const float* base, int bytes, int 
 __device__ __forceinline__ void merge_chunks_and_store(const DecodeParams& p, int seq, int kvh, int n_live, int G,
                                                        int tid, int nthreads)
 {
-    constexpr int kBatch = 8;
     const long long chunk_rows = (long long)p.hq;                       // rows between consecutive chunks
     const long long prow0 = (long long)seq * p.max_chunks * p.hq + (long long)kvh * G;
     const long long orow0 = (long long)seq * p.hq + (long long)kvh * G;
-    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
-        const int g = idx >> 5, d = (idx & 31) * 4;
-        const float* l = p.part_lse + prow0 + g;
-        float m = -INFINITY;
-        for (int c = 0; c < n_live; c += kBatch) {
-            float v[kBatch];
+    int r0[3], r1[3];
+    ext_row_ranges(p, seq, r0, r1);
+    for (int base = tid; base < G * (kD / 4); base += nthreads * kMergeLanes) {
+        RowAcc a[kMergeLanes];
+        bool on[kMergeLanes];
+        int g[kMergeLanes], d[kMergeLanes], head[kMergeLanes];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                v[u] = (c + u < n_live) ? __hip_atomic_load(l + (c + u) * chunk_rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                        : -INFINITY;
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) m = fmaxf(m, v[u]);
+        for (int k = 0; k < kMergeLanes; ++k) {
+            const int idx = base + k * nthreads;
+            on[k] = idx < G * (kD / 4);
+            g[k] = on[k] ? idx >> 5 : 0;
+            d[k] = (idx & 31) * 4;
+            head[k] = kvh * G + g[k];
+            a[k].start(f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
         }
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-        float lse = -INFINITY;
-        if (m != -INFINITY) {
-            float wsum = 0.f;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int c = 0; c < n_live; c += kBatch) {
-                float w[kBatch];
-                f32x4 x[kBatch];
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const float v = (c + u < n_live) ? __hip_atomic_load(l + (c + u) * chunk_rows, __ATOMIC_RELAXED,
-                                                                         __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
-                    w[u] = (v == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((v - m) * kLog2e);
-                }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (w[u] != 0.f)
-                        x[u] = load_shared4(p.part_o + (prow0 + (c + u) * chunk_rows) * kD, G * kD * 4, (g * kD + d) * 4);
-                }
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u) { wsum += w[u]; acc += w[u] * x[u]; }
-            }
-            o = acc * (1.f / wsum);
-            lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+        for (int c = 0; c < n_live; c += kMergeTile) {
+            merge_tile(a, on, min(kMergeTile, n_live - c),
+                       [&](int k, int u) {
+                           return __hip_atomic_load(p.part_lse + prow0 + g[k] + (c + u) * chunk_rows, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+                       },
+                       [&](int k, int u) {
+                           return load_shared4(p.part_o + (prow0 + (c + u) * chunk_rows) * kD, G * kD * 4,
+                                               (g[k] * kD + d[k]) * 4);
+                       });
         }
-        if (p.n_ext > 0) fold_ext_rows(p, seq, kvh * G + g, d, o, lse);
-        store_final_quad(p, orow0 + g, d, o, lse);
+        if (p.n_ext > 0) fold_ext_rows(p, r0, r1, a, on, head, d);
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            if (!on[k]) continue;
+            f32x4 o;
+            float lse;
+            a[k].finish(o, lse);
+            store_final_quad(p, orow0 + g[k], d[k], o, lse);
+        }
     }
 }
 
-// after a barrier: merge the states of waves w0 .. w1-1 with the log-sum-exp rule and write the item's rows
-// (only seq, chunk and kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn
-__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
-                                                  int tid, int nthreads, int mode, int w0 = 0, int w1 = kWaves)
+// after a barrier: merge the states of waves w0 .. w1-1 with the log-sum-exp rule into the item's rows
+// (only seq, chunk and kvh of `it` are used): four dims of one head, at position idx of the G x 32
+__device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, int w0, int w1, f32x4& o, float& lse)
 {
     const float* sh_acc = lds;
     const float* sh_m = lds + kWaves * G * kD;
     const float* sh_l = sh_m + kWaves * 16;
+    const int g = idx >> 5, d = (idx & 31) * 4;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int w = w0; w < w1; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
+    o = f32x4{0.f, 0.f, 0.f, 0.f};
+    lse = -INFINITY;
+    if (mm != -INFINITY) {
+        float ll = 0.f;
+        f32x4 oo = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = w0; w < w1; ++w) {
+            const float mw = sh_m[w * 16 + g];
+            const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
+            ll += f * sh_l[w * 16 + g];
+            oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + combine_slot(g, d));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
+        lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
+    }
+}
+
+// ... and their stores; thread `tid` of `nthreads` takes four dims of one head per turn
+__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
+                                                  int tid, int nthreads, int mode, int w0 = 0, int w1 = kWaves)
+{
     const bool final_row = mode == kRowFinal || mode == kRowFinalFold;
     // a final row is also kept as a partial one when the call has a single chunk slot and a partial buffer
     const bool partial_row = !final_row || p.max_chunks == 1;
     const long long prow0 = ((long long)it.seq * p.max_chunks + it.chunk) * p.hq + (long long)it.kvh * G;
     const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
-    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
-        const int g = idx >> 5, d = (idx & 31) * 4;
-        float mm = -INFINITY;
-#pragma unroll
-        for (int w = w0; w < w1; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-        float lse = -INFINITY;
-        if (mm != -INFINITY) {
-            float ll = 0.f;
-            f32x4 oo = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = w0; w < w1; ++w) {
-                const float mw = sh_m[w * 16 + g];
-                const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
-                ll += f * sh_l[w * 16 + g];
-                oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + combine_slot(g, d));
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
-            lse = (mm + __builtin_amdgcn_logf(ll)) * kLn2;           // v_log_f32 is log2
-            if (p.part_o && partial_row) {
-                if (mode == kRowShared) store_shared4(p.part_o + prow0 * kD, G * kD * 4, (g * kD + d) * 4, o);
-                else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
-            }
+    auto store_partial = [&](int g, int d, f32x4 o, float lse) {
+        if (p.part_o && partial_row && lse != -INFINITY) {
+            if (mode == kRowShared) store_shared4(p.part_o + prow0 * kD, G * kD * 4, (g * kD + d) * 4, o);
+            else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
         }
         // 4 G bytes: a plain store, so that the L2 can fill the line; the slot of a row that went out as a
         // final row holds no partial
@@ -697,9 +738,48 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             if (mode == kRowShared) __hip_atomic_store(p.part_lse + prow0 + g, lse, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             else p.part_lse[prow0 + g] = partial_row ? lse : -INFINITY;
         }
-        if (final_row) {
-            if (mode == kRowFinalFold) fold_ext_rows(p, it.seq, it.kvh * G + g, d, o, lse);
-            store_final_quad(p, orow0 + g, d, o, lse);
+    };
+    if (mode != kRowFinalFold) {
+        for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
+            const int g = idx >> 5, d = (idx & 31) * 4;
+            f32x4 o;
+            float lse;
+            combine_quad(lds, G, idx, w0, w1, o, lse);
+            store_partial(g, d, o, lse);
+            if (final_row) store_final_quad(p, orow0 + g, d, o, lse);
+        }
+        return;
+    }
+    // the final row after folding in what other sources hold for the sequence
+    int r0[3], r1[3];
+    ext_row_ranges(p, it.seq, r0, r1);
+    for (int base = tid; base < G * (kD / 4); base += nthreads * kMergeLanes) {
+        RowAcc a[kMergeLanes];
+        bool on[kMergeLanes];
+        int g[kMergeLanes], d[kMergeLanes], head[kMergeLanes];
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            const int idx = base + k * nthreads;
+            on[k] = idx < G * (kD / 4);
+            g[k] = on[k] ? idx >> 5 : 0;
+            d[k] = (idx & 31) * 4;
+            head[k] = it.kvh * G + g[k];
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            float lse = -INFINITY;
+            if (on[k]) {
+                combine_quad(lds, G, idx, w0, w1, o, lse);
+                store_partial(g[k], d[k], o, lse);
+            }
+            a[k].start(o, lse);
+        }
+        fold_ext_rows(p, r0, r1, a, on, head, d);
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            if (!on[k]) continue;
+            f32x4 o;
+            float lse;
+            a[k].finish(o, lse);
+            store_final_quad(p, orow0 + g[k], d[k], o, lse);
         }
     }
 }
@@ -711,16 +791,32 @@ __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int 
                                             int tid, int nthreads, bool final_here)
 {
     const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + head0;
-    const long long orow0 = (long long)seq * p.hq + head0;
     if (p.part_lse)
         for (int h = tid; h < heads; h += nthreads) p.part_lse[prow0 + h] = -INFINITY;
     if (final_here) {
-        for (int idx = tid; idx < heads * (kD / 4); idx += nthreads) {
-            const int g = idx >> 5, d = (idx & 31) * 4;
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-            float lse = -INFINITY;
-            if (p.n_ext > 0) fold_ext_rows(p, seq, head0 + g, d, o, lse);
-            store_final_quad(p, orow0 + g, d, o, lse);
+        int r0[3], r1[3];
+        ext_row_ranges(p, seq, r0, r1);
+        for (int base = tid; base < heads * (kD / 4); base += nthreads * kMergeLanes) {
+            RowAcc a[kMergeLanes];
+            bool on[kMergeLanes];
+            int d[kMergeLanes], head[kMergeLanes];
+#pragma unroll
+            for (int k = 0; k < kMergeLanes; ++k) {
+                const int idx = base + k * nthreads;
+                on[k] = idx < heads * (kD / 4);
+                head[k] = head0 + (on[k] ? idx >> 5 : 0);
+                d[k] = (idx & 31) * 4;
+                a[k].start(f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
+            }
+            if (p.n_ext > 0) fold_ext_rows(p, r0, r1, a, on, head, d);
+#pragma unroll
+            for (int k = 0; k < kMergeLanes; ++k) {
+                if (!on[k]) continue;
+                f32x4 o;
+                float lse;
+                a[k].finish(o, lse);
+                store_final_quad(p, (long long)seq * p.hq + head[k], d[k], o, lse);
+            }
         }
     }
 }
@@ -948,13 +1044,19 @@ __host__ __device__ __forceinline__ bool ticket_index(const TicketSpace& ts, uns
     return idx < ts.n_items;
 }
 
-__device__ __forceinline__ TicketSpace ticket_space(const DecodeParams& p, const unsigned* __restrict__ counts)
-{
-    return make_ticket_space(min(counts[0], (unsigned)(p.batch * p.max_chunks)), counts[5], (unsigned)p.hkv, gridDim.x);
-}
+// Where a launch finds its work list: in the workspace (written by decode_list_kernel), or in the
+// workgroup's own LDS (built by every workgroup for itself at the start of the launch, see build_list_lds).
+struct ListView {
+    bool in_lds;
+    const WorkEntry* entries;          // workspace list: non-empty entries from the front, empty ones from the back
+    const unsigned* lds_entry;         // LDS list: sequence << 16 | chunk; non-empty entries first, then the empty ones
+    const int* lds_b;                  // LDS list: clamped range of every sequence
+    const int* lds_e;
+    unsigned n_live, n_empty, n_long;  // non-empty entries, empty entries, non-empty entries longer than kShortTokens
+};
 
 // this wave's item under a ticket (ticket < n_tickets); n_steps = 0 if the wave has none
-__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
+__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const ListView& lv,
                                             const int* __restrict__ block_table, const TicketSpace& ts,
                                             unsigned ticket, int wave)
 {
@@ -962,18 +1064,29 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     unsigned idx;
     const bool valid = ticket_index(ts, ticket, wave, idx, grouped);
     idx = valid ? idx : ts.n_items - 1u;
-    const WorkEntry w = load_invariant(entries + idx / (unsigned)p.hkv);
     Item it;
     it.kvh = (int)(idx % (unsigned)p.hkv);
-    // A list that was planned for these very ranges holds only values that pass unchanged; one reused
-    // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are the
-    // worst that can come of it, never an access outside the table or the output buffers.
-    const int cap = p.max_blocks * kBlockSize;
-    it.seq = min(max(w.seq, 0), p.batch - 1);
-    it.chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
-    it.n_live = min(max((int)((unsigned)w.chunk >> 16), 1), p.max_chunks);
-    it.cb = min(max(w.cb, 0), cap - 1);
-    it.ce = min(max(w.ce, it.cb + 1), cap);
+    if (lv.in_lds) {
+        // (read with instructions of their own, like the ticket slots: see lds_peek)
+        const unsigned packed = (unsigned)uniform((int)lds_peek(lv.lds_entry + idx / (unsigned)p.hkv));
+        it.seq = (int)(packed >> 16);
+        it.chunk = (int)(packed & 0xffffu);
+        const int b = uniform((int)lds_peek(reinterpret_cast<const unsigned*>(lv.lds_b + it.seq)));
+        const int e = uniform((int)lds_peek(reinterpret_cast<const unsigned*>(lv.lds_e + it.seq)));
+        chunk_range(p, b, e, it.chunk, it.cb, it.ce);
+        it.n_live = live_chunks(p, b, e);
+    } else {
+        const WorkEntry w = load_invariant(lv.entries + idx / (unsigned)p.hkv);
+        // A list that was planned for these very ranges holds only values that pass unchanged; one reused
+        // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are
+        // the worst that can come of it, never an access outside the table or the output buffers.
+        const int cap = p.max_blocks * kBlockSize;
+        it.seq = min(max(w.seq, 0), p.batch - 1);
+        it.chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
+        it.n_live = min(max((int)((unsigned)w.chunk >> 16), 1), p.max_chunks);
+        it.cb = min(max(w.cb, 0), cap - 1);
+        it.ce = min(max(w.ce, it.cb + 1), cap);
+    }
     finish_item(it, block_table, p.max_blocks);
     it.s0 = grouped ? 0 : wave;
     it.ds = grouped ? 1 : kWaves;
@@ -981,8 +1094,114 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     return it;
 }
 
+// ---- the work list built inside the attention launch ---------------------------------------------------
+// When the list is small enough, every workgroup builds it for itself in LDS at the start of the launch
+// instead of reading one that a launch of its own wrote to the workspace: the same longest-first counting
+// sort, but stable (an entry's place among the entries of its sort bin is its index order), so that all
+// workgroups arrive at the identical list without talking to each other.  What it saves is the list
+// kernel and the gap between the two launches (about 7 us per step), and one trip to memory at every
+// hand-over (the next item's entry now comes from LDS).
+// LDS layout (32-bit words): 8 header words (non-empty entries, empty entries, long entries), the clamped
+// ranges b[batch] and e[batch], kListWaves x (kSortBins + 1) counters, then the entries.
+constexpr int kListWaves = kPersistentThreads / kWave;
+constexpr int kListHeaderWords = 8;
+constexpr int kListMaxEntries = 8192;
+constexpr int kListMaxBatch = 4096;
+
+__host__ __device__ __forceinline__ size_t list_lds_bytes(long long batch, long long max_chunks)
+{
+    return (size_t)(kListHeaderWords + 2 * batch + kListWaves * (kSortBins + 1) + batch * max_chunks) * 4;
+}
+
+// all kPersistentThreads threads of the workgroup; ends with a barrier
+__device__ __forceinline__ ListView build_list_lds(const DecodeParams& p, unsigned* area)
+{
+    unsigned* hdr = area;
+    int* lb = reinterpret_cast<int*>(area + kListHeaderWords);
+    int* le = lb + p.batch;
+    unsigned* hist = reinterpret_cast<unsigned*>(le + p.batch);
+    unsigned* ent = hist + kListWaves * (kSortBins + 1);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int total = p.batch * p.max_chunks;
+    const float bins_per_page = sort_bins_per_page(p.chunk_tokens);
+    for (int i = tid; i < p.batch; i += kPersistentThreads) {
+        int b, e;
+        seq_range(p, i, b, e);
+        lb[i] = b;
+        le[i] = e;
+    }
+    for (int i = tid; i < kListWaves * (kSortBins + 1); i += kPersistentThreads) hist[i] = 0;
+    __syncthreads();
+    // every wave takes a contiguous block of entries (whole rounds of 64), in index order
+    const int per = (((total + kListWaves - 1) / kListWaves) + kWave - 1) / kWave * kWave;
+    const int first = wave * per, last = min(total, first + per);
+    unsigned* my_hist = hist + wave * (kSortBins + 1);
+    auto key_of = [&](int e, unsigned& packed) {
+        const int seq = e / p.max_chunks, chunk = e - seq * p.max_chunks;
+        int cb, ce;
+        chunk_range(p, lb[seq], le[seq], chunk, cb, ce);
+        packed = ((unsigned)seq << 16) | (unsigned)chunk;
+        return ce > cb ? sort_bin(ce - cb, bins_per_page) : kSortBins;
+    };
+    for (int e = first + lane; e < last; e += kWave) {
+        unsigned packed;
+        atomicAdd(&my_hist[key_of(e, packed)], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // exclusive scan over (bin, wave) in that order: where each wave's entries of each bin start
+        constexpr int kCount = kListWaves * (kSortBins + 1);
+        constexpr int kPer = (kCount + kWave - 1) / kWave;
+        unsigned c[kPer], sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int j = lane * kPer + i;
+            c[i] = j < kCount ? hist[(j % kListWaves) * (kSortBins + 1) + j / kListWaves] : 0u;
+            sum += c[i];
+        }
+        unsigned incl = sum;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const unsigned up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        unsigned run = incl - sum;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int j = lane * kPer + i;
+            if (j < kCount) {
+                if (j == kSortBins * kListWaves) { hdr[0] = run; hdr[1] = (unsigned)total - run; }
+                if (j == kLongBins * kListWaves) hdr[2] = run;
+                hist[(j % kListWaves) * (kSortBins + 1) + j / kListWaves] = run;
+            }
+            run += c[i];
+        }
+    }
+    __syncthreads();
+    // an entry's slot: its wave's running counter of its bin; lanes of one round that share a bin are
+    // served in lane order, rounds follow each other in program order
+    for (int e = first + lane; e < last; e += kWave) {
+        unsigned packed;
+        const int key = key_of(e, packed);
+        const unsigned slot = atomicAdd(&my_hist[key], 1u);
+        ent[slot] = packed;
+    }
+    __syncthreads();
+    ListView lv;
+    lv.in_lds = true;
+    lv.entries = nullptr;
+    lv.lds_entry = ent;
+    lv.lds_b = lb;
+    lv.lds_e = le;
+    lv.n_live = (unsigned)uniform((int)hdr[0]);
+    lv.n_empty = (unsigned)uniform((int)hdr[1]);
+    lv.n_long = (unsigned)uniform((int)hdr[2]);
+    return lv;
+}
+
 constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming waves tell the writer about an item
 
+// `entries` == nullptr: the list is built in LDS by the workgroup itself
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
@@ -997,7 +1216,20 @@ __device__ __forceinline__ void persistent_body(
     char* const q_base = stage_base + kWaves * kStageBytes;          // [parity][wave] buffers of G rows
     const int q_bytes = p.group * kD * 2;
     const LaneIds id(stage_base);
-    const TicketSpace ts = ticket_space(p, counts);
+    ListView lv;
+    if (entries == nullptr) {
+        lv = build_list_lds(p, reinterpret_cast<unsigned*>(q_base + 2 * kWaves * q_bytes));
+    } else {
+        const unsigned total = (unsigned)(p.batch * p.max_chunks);
+        lv.in_lds = false;
+        lv.entries = entries;
+        lv.lds_entry = nullptr;
+        lv.lds_b = lv.lds_e = nullptr;
+        lv.n_live = min(counts[0], total);
+        lv.n_empty = min(counts[1], total);
+        lv.n_long = counts[5];
+    }
+    const TicketSpace ts = make_ticket_space(lv.n_live, lv.n_long, (unsigned)p.hkv, gridDim.x);
     const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
 
@@ -1005,12 +1237,18 @@ __device__ __forceinline__ void persistent_body(
     // only, shared out over the resident workgroups); and which sequences this call finishes
     auto store_empty_share = [&] {
         const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
-        const unsigned n_empty = min(counts[1], last + 1u);
-        for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
-            const WorkEntry w = load_invariant(entries + (last - i));
-            const int chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
-            store_empty(p, min(max(w.seq, 0), p.batch - 1), chunk, 0, p.hq, id.lane, kWave,
-                        p.out_o != nullptr && chunk == 0);
+        for (unsigned i = blockIdx.x; i < lv.n_empty; i += gridDim.x) {
+            int seq, chunk;
+            if (lv.in_lds) {
+                const unsigned packed = lv.lds_entry[lv.n_live + i];
+                seq = (int)(packed >> 16);
+                chunk = (int)(packed & 0xffffu);
+            } else {
+                const WorkEntry w = load_invariant(entries + (last - i));
+                seq = min(max(w.seq, 0), p.batch - 1);
+                chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
+            }
+            store_empty(p, uniform(seq), uniform(chunk), 0, p.hq, id.lane, kWave, p.out_o != nullptr && chunk == 0);
         }
         if (p.seq_final) {
             for (int i = blockIdx.x * kWave + id.lane; i < p.batch; i += gridDim.x * kWave) {
@@ -1110,7 +1348,7 @@ __device__ __forceinline__ void persistent_body(
 
     // first ticket: Q goes into LDS, every wave requests its first step, then all read Q; the stores for
     // the empty rows go out while those first loads are on their way
-    Item it = ticket_item(p, entries, block_table, ts, tk, id.wave);
+    Item it = ticket_item(p, lv, block_table, ts, tk, id.wave);
     if (threadIdx.x == 0) {
         sh_ticket[0] = kPending;
         sh_ticket[2] = kPending;
@@ -1157,7 +1395,7 @@ __device__ __forceinline__ void persistent_body(
             if (tn == kPending) gave_up = true;
             has_next = tn < n_tickets;
             if (has_next) {
-                nx = ticket_item(p, entries, block_table, ts, tn, id.wave);
+                nx = ticket_item(p, lv, block_table, ts, tn, id.wave);
                 if (has_steps(nx)) tail = Tail{true, nx.kvh, step_pages(p, nx, nx.s0)};
                 // the table reads for the wave's second step of that item go out now as well: at the
                 // item's start they would be a cold round trip in front of its second request
@@ -1254,6 +1492,16 @@ size_t lds_bytes(int group, bool persistent)
     return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)kWaves * group * kD * 2;
 }
 
+// dynamic LDS a workgroup may ask for: the CU's 160 KiB less the kernel's static words
+constexpr size_t kMaxDynamicLds = 160 * 1024 - 512;
+
+// whether a launch can build its list in LDS (then after the persistent form's other areas)
+bool list_fits_lds(const DecodeParams& p)
+{
+    return p.batch <= kListMaxBatch && (long long)p.batch * p.max_chunks <= kListMaxEntries &&
+           lds_bytes(p.group, true) + list_lds_bytes(p.batch, p.max_chunks) <= kMaxDynamicLds;
+}
+
 }  // namespace
 
 bool decode_mfma_supports(const DecodeParams& p, bool bf16)
@@ -1319,7 +1567,7 @@ hipError_t device_facts(int& cus)
     DeviceFacts& f = facts[dev];
     if (!f.known) {
         f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
+        const int lds_p = (int)kMaxDynamicLds, lds_g = (int)lds_bytes(16, false);
         if (f.status == hipSuccess)
             f.status = hipFuncSetAttribute((const void*)decode_mfma_persistent_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
@@ -1356,6 +1604,11 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
         e = launch_decode_plan(p, workspace, s);
         if (e != hipSuccess) return e;
     }
+    // A workspace that is known to be in order (planned: its counters are at rest, as omni_decode_plan and
+    // every finished launch leave them) lets the launch build a small list by itself; otherwise the list
+    // kernel has just put both in place.
+    const bool self_list = planned && list_fits_lds(p);
+    const size_t lds_all = lds + (self_list ? list_lds_bytes(p.batch, p.max_chunks) : 0);
     // One workgroup per CU.  More would fit (three), but the memory system is saturated by four waves
     // per CU already, and a CU serves its oldest waves first: a second and third workgroup get a
     // fraction of the first one's bandwidth, start late and finish late, which costs more at both ends
@@ -1363,8 +1616,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
-    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p,
-                       p.block_table, header, header + 1, entries, arrivals);
+    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds_all, s, p,
+                       p.block_table, header, header + 1, self_list ? nullptr : entries, arrivals);
     return hipGetLastError();
 }
 

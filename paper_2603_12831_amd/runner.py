@@ -32,6 +32,10 @@ class DeviceWorkload:
         "final"  the decode call also writes the final rows of the sequences it can finish (one non-empty
                  chunk), the masked merge does the others;
         "fused"  the decode call finishes every sequence (in-launch merge, external rows folded in)."""
+        # workspace: False / 0 none (grid form), True / 1 a workspace whose list every call rebuilds,
+        # 2 a workspace prepared once by omni_decode_plan and passed as planned to every call
+        self.plan_first = workspace == 2 and workspace is not True
+        self._planned = False
         if mode not in ("merge", "final", "fused"):
             raise ValueError("unknown mode %r" % mode)
         if mode != "merge" and len(w.calls) != 1:
@@ -119,7 +123,10 @@ class DeviceWorkload:
 
     def run(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
         """One pass of the whole hot path: every decode call, then the merge."""
-        self.run_attention(kernel, pool, stream)
+        if self.plan_first and not self._planned:
+            self.plan(stream)
+            self._planned = True
+        self.run_attention(kernel, pool, stream, planned=self.plan_first)
         self.run_merge(stream)
 
     def abandoned_waves(self) -> int:
