@@ -88,7 +88,8 @@ typedef const __attribute__((address_space(1))) void global_void;
 
 struct Item {                // wave-uniform description of a work item
     int seq, chunk, kvh, cb, ce, lp_first, lp_last, n_steps;
-    int n_live;              // non-empty chunks of the item's sequence (the item's own included)
+    // `chunk`: the chunk index in the low 16 bits, the number of non-empty chunks of the item's sequence (its
+    // own included) in the high 16 (one word, to keep the streaming loop's scalar registers down)
     int s0, ds;              // this wave's steps of the item: s0, s0 + ds, ... (ds = 1: the item is this wave's alone)
     const int* __restrict__ table;
 };
@@ -106,6 +107,10 @@ __device__ __forceinline__ WorkEntry load_invariant(const WorkEntry* ptr)
     const i32x4 v = *(const __attribute__((address_space(4))) i32x4*)ptr;
     return WorkEntry{v[0], v[1], v[2], v[3]};
 }
+
+__device__ __forceinline__ int pack_chunk(int chunk, int n_live) { return (int)((unsigned)chunk | ((unsigned)n_live << 16)); }
+__device__ __forceinline__ int chunk_index(int packed) { return packed & 0xffff; }
+__device__ __forceinline__ int chunk_live(int packed) { return (int)((unsigned)packed >> 16); }
 
 struct Pages { long long a, b; };                      // physical pages of a step, -1 = absent
 
@@ -234,7 +239,7 @@ __device__ __forceinline__ void make_uniform(Item& it)
     it.seq = uniform(it.seq); it.chunk = uniform(it.chunk); it.kvh = uniform(it.kvh);
     it.cb = uniform(it.cb); it.ce = uniform(it.ce);
     it.lp_first = uniform(it.lp_first); it.lp_last = uniform(it.lp_last); it.n_steps = uniform(it.n_steps);
-    it.s0 = uniform(it.s0); it.ds = uniform(it.ds); it.n_live = uniform(it.n_live);
+    it.s0 = uniform(it.s0); it.ds = uniform(it.ds);
     const unsigned long long t = reinterpret_cast<unsigned long long>(it.table);
     const unsigned lo = (unsigned)uniform((int)(unsigned)t), hi = (unsigned)uniform((int)(unsigned)(t >> 32));
     it.table = reinterpret_cast<const int*>(((unsigned long long)hi << 32) | (unsigned long long)lo);
@@ -505,117 +510,24 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
-// Running merge of partial rows for four dims of one head, by the disjoint-union identity of Eq. 1 in its
-// incremental form (natural-log units): acc = sum w_r O_r and wsum = sum w_r with w_r = exp(LSE_r - m).
-struct RowAcc {
-    float m, wsum;
-    f32x4 acc;
-    __device__ __forceinline__ void start(f32x4 o, float lse)   // a normalised row (o, lse); lse = -inf: nothing yet
-    {
-        m = lse;
-        wsum = lse == -INFINITY ? 0.f : 1.f;
-        acc = lse == -INFINITY ? f32x4{0.f, 0.f, 0.f, 0.f} : o;
-    }
-    __device__ __forceinline__ void finish(f32x4& o, float& lse) const
-    {
-        if (m == -INFINITY) { o = f32x4{0.f, 0.f, 0.f, 0.f}; lse = -INFINITY; return; }
-        o = acc * (1.f / wsum);
-        lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
-    }
-};
-
-constexpr int kMergeLanes = 2;     // (head, four dims) positions a lane merges side by side
-constexpr int kMergeTile = 8;      // rows per round trip
-
-// Adds rows 0 .. n-1 (n <= kMergeTile) of some source to the kMergeLanes running merges of a lane.  All
-// LSE values and all O pieces of the tile are requested before anything is used: one memory round trip per
-// tile, whatever the weights turn out to be (the writer wave's merges are chains of such trips, and their
-// number is what they cost).  A row of weight zero (LSE = -inf) is fetched like the others but never enters
-// the sums, so whatever its O holds (it may never have been written) does no harm.
-template <class LseAt, class OAt>
-__device__ __forceinline__ void merge_tile(RowAcc (&a)[kMergeLanes], const bool (&on)[kMergeLanes], int n,
-                                           LseAt&& lse_at, OAt&& o_at)
-{
-    float l[kMergeLanes][kMergeTile];
-    f32x4 x[kMergeLanes][kMergeTile];
-#pragma unroll
-    for (int k = 0; k < kMergeLanes; ++k)
-#pragma unroll
-        for (int u = 0; u < kMergeTile; ++u) l[k][u] = (on[k] && u < n) ? lse_at(k, u) : -INFINITY;
-#pragma unroll
-    for (int k = 0; k < kMergeLanes; ++k)
-#pragma unroll
-        for (int u = 0; u < kMergeTile; ++u) x[k][u] = (on[k] && u < n) ? o_at(k, u) : f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < kMergeLanes; ++k) {
-        float m_new = a[k].m;
-#pragma unroll
-        for (int u = 0; u < kMergeTile; ++u) m_new = fmaxf(m_new, l[k][u]);
-        if (m_new == -INFINITY) continue;
-        const float keep = a[k].m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((a[k].m - m_new) * kLog2e);
-        a[k].acc *= keep;
-        a[k].wsum *= keep;
-        a[k].m = m_new;
-#pragma unroll
-        for (int u = 0; u < kMergeTile; ++u) {
-            const bool live = l[k][u] != -INFINITY;
-            const float w = live ? __builtin_amdgcn_exp2f((l[k][u] - m_new) * kLog2e) : 0.f;
-            a[k].wsum += w;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) a[k].acc[c] += live ? w * x[k][u][c] : 0.f;
-        }
-    }
-}
-
-// Rows [r0, r1) of the sources of rows computed elsewhere (r0 / r1 per source: the rows of one sequence)
-// into the running merges of positions (head[k], dims d[k] .. d[k]+3).
-__device__ __forceinline__ void fold_ext_rows(const DecodeParams& p, const int (&r0)[3], const int (&r1)[3],
-                                              RowAcc (&a)[kMergeLanes], const bool (&on)[kMergeLanes],
-                                              const int (&head)[kMergeLanes], const int (&d)[kMergeLanes])
-{
-#pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        if (s >= p.n_ext) break;
-        const float* lse = p.ext[s].lse;
-        const float* orow = p.ext[s].o;
-        for (int r = r0[s]; r < r1[s]; r += kMergeTile) {
-            merge_tile(a, on, min(kMergeTile, r1[s] - r),
-                       [&](int k, int u) { return lse[(long long)(r + u) * p.hq + head[k]]; },
-                       [&](int k, int u) {
-                           return *reinterpret_cast<const f32x4*>(orow + ((long long)(r + u) * p.hq + head[k]) * kD + d[k]);
-                       });
-        }
-    }
-}
-
-// rows of sequence `seq` in every source of rows computed elsewhere (wave-uniform)
-__device__ __forceinline__ void ext_row_ranges(const DecodeParams& p, int seq, int (&r0)[3], int (&r1)[3])
-{
-#pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        r0[s] = r1[s] = 0;
-        if (s < p.n_ext) src_rows(p.ext[s], seq, r0[s], r1[s]);
-    }
-}
-
 // four dims of a final row (row = sequence * Hq + head)
-__device__ __forceinline__ void store_final_quad(const DecodeParams& p, long long row, int d, f32x4 o, float lse)
+__device__ __forceinline__ void store_final_quad(void* out_o, float* out_lse, bool out_bf16, long long row, int d,
+                                                 f32x4 o, float lse)
 {
-    if (p.out_bf16) {
+    if (out_bf16) {
         uint2 pk;
         pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
         pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
-        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out_o) + row * kD + d) = pk;
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out_o) + row * kD + d) = pk;
     } else {
-        *reinterpret_cast<f32x4*>(static_cast<float*>(p.out_o) + row * kD + d) = o;
+        *reinterpret_cast<f32x4*>(static_cast<float*>(out_o) + row * kD + d) = o;
     }
-    if (p.out_lse && d == 0) p.out_lse[row] = lse;
+    if (out_lse && d == 0) out_lse[row] = lse;
 }
 
 // What becomes of an item's rows: a partial row for a later merge; the sequence's final row (the item is
 // the sequence's only non-empty chunk); the final row after folding in the rows other sources hold for
-// the sequence.
-// kRowShared: a partial row that another workgroup of this launch will read (the fused form: whoever
+// the sequence; a partial row that another workgroup of this launch will read (the fused form: whoever
 // finishes a sequence's last chunk merges them all).
 enum RowMode { kRowPartial = 0, kRowFinal = 1, kRowFinalFold = 2, kRowShared = 3 };
 
@@ -636,61 +548,9 @@ __device__ __forceinline__ void store_shared4(float* base, int bytes, int off, f
     constexpr int kDeviceScopeNt = (1 << 4) | (1 << 1);
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), byte_buffer(base, bytes), off, 0, kDeviceScopeNt);
 }
-__device__ __forceinline__ f32x4 load_shared4(const float* base, int bytes, int off)
-{
-    constexpr int kDeviceScope = 1 << 4;
-    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(byte_buffer(base, bytes), off, 0, kDeviceScope));
-}
 
-// The fused form's merge: the partial rows of chunks 0 .. n_live-1 of (sequence, kv head), written by this
-// and other workgroups of the launch, then whatever other sources hold for the sequence, into the final
-// rows of the G heads.  Chunk order, so the result does not depend on which workgroup came last.
-__device__ __forceinline__ void merge_chunks_and_store(const DecodeParams& p, int seq, int kvh, int n_live, int G,
-                                                       int tid, int nthreads)
-{
-    const long long chunk_rows = (long long)p.hq;                       // rows between consecutive chunks
-    const long long prow0 = (long long)seq * p.max_chunks * p.hq + (long long)kvh * G;
-    const long long orow0 = (long long)seq * p.hq + (long long)kvh * G;
-    int r0[3], r1[3];
-    ext_row_ranges(p, seq, r0, r1);
-    for (int base = tid; base < G * (kD / 4); base += nthreads * kMergeLanes) {
-        RowAcc a[kMergeLanes];
-        bool on[kMergeLanes];
-        int g[kMergeLanes], d[kMergeLanes], head[kMergeLanes];
-#pragma unroll
-        for (int k = 0; k < kMergeLanes; ++k) {
-            const int idx = base + k * nthreads;
-            on[k] = idx < G * (kD / 4);
-            g[k] = on[k] ? idx >> 5 : 0;
-            d[k] = (idx & 31) * 4;
-            head[k] = kvh * G + g[k];
-            a[k].start(f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
-        }
-        for (int c = 0; c < n_live; c += kMergeTile) {
-            merge_tile(a, on, min(kMergeTile, n_live - c),
-                       [&](int k, int u) {
-                           return __hip_atomic_load(p.part_lse + prow0 + g[k] + (c + u) * chunk_rows, __ATOMIC_RELAXED,
-                                                    __HIP_MEMORY_SCOPE_AGENT);
-                       },
-                       [&](int k, int u) {
-                           return load_shared4(p.part_o + (prow0 + (c + u) * chunk_rows) * kD, G * kD * 4,
-                                               (g[k] * kD + d[k]) * 4);
-                       });
-        }
-        if (p.n_ext > 0) fold_ext_rows(p, r0, r1, a, on, head, d);
-#pragma unroll
-        for (int k = 0; k < kMergeLanes; ++k) {
-            if (!on[k]) continue;
-            f32x4 o;
-            float lse;
-            a[k].finish(o, lse);
-            store_final_quad(p, orow0 + g[k], d[k], o, lse);
-        }
-    }
-}
-
-// after a barrier: merge the states of waves w0 .. w1-1 with the log-sum-exp rule into the item's rows
-// (only seq, chunk and kvh of `it` are used): four dims of one head, at position idx of the G x 32
+// after a barrier: the states of waves w0 .. w1-1 merged with the log-sum-exp rule into four dims of one
+// head of the item's row, at position idx of the G x 32
 __device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, int w0, int w1, f32x4& o, float& lse)
 {
     const float* sh_acc = lds;
@@ -698,14 +558,12 @@ __device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, i
     const float* sh_l = sh_m + kWaves * 16;
     const int g = idx >> 5, d = (idx & 31) * 4;
     float mm = -INFINITY;
-#pragma unroll
     for (int w = w0; w < w1; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
     o = f32x4{0.f, 0.f, 0.f, 0.f};
     lse = -INFINITY;
     if (mm != -INFINITY) {
         float ll = 0.f;
         f32x4 oo = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
         for (int w = w0; w < w1; ++w) {
             const float mw = sh_m[w * 16 + g];
             const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
@@ -718,16 +576,252 @@ __device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, i
     }
 }
 
-// ... and their stores; thread `tid` of `nthreads` takes four dims of one head per turn
-__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
-                                                  int tid, int nthreads, int mode, int w0 = 0, int w1 = kWaves)
+// ---- the merges inside the launch (fused form) ----------------------------------------------------------
+// One routine turns everything that is known about G heads of a sequence into their final rows: the item's own state still in LDS (if any), the
+// partial rows of the sequence's chunks written by this and other workgroups (if any), and the rows other
+// sources hold for the sequence.  Rule: the disjoint-union identity of Eq. 1 in incremental form,
+// acc = sum w_r O_r and wsum = sum w_r with w_r = exp(LSE_r - m), in a fixed order of rows, so the result
+// does not depend on which workgroup runs it.
+struct MergeJob {
+    void* out_o;                   // final rows
+    float* out_lse;                // may be null
+    const float* part_o;           // chunk rows of the call (n_chunks > 0)
+    const float* part_lse;
+    const float* ext_o[3];         // rows computed elsewhere: rows r0 .. r1-1 of each source
+    const float* ext_lse[3];
+    int r0[3], r1[3];
+    const float* own_lds;          // combine area holding the item's own state (null: none)
+    int w0, w1;                    //   waves whose states make it up
+    int hq, max_chunks, out_bf16, n_ext;
+    int seq, head0, heads, group;  // rows [head0, head0 + heads) of the sequence; `group` = G of the launch
+    int n_chunks;                  // chunks 0 .. n_chunks-1 of (seq, kv head head0 / G) hold partial rows
+};
+
+struct RowAcc {
+    float m, wsum;
+    f32x4 acc;
+};
+
+constexpr int kMergeLanes = 2;     // (head, four dims) positions a lane merges side by side
+constexpr int kMergeTile = 8;      // rows per round trip
+
+// Adds rows 0 .. n-1 (n <= kMergeTile) of one source to the kMergeLanes running merges of a lane: row r of
+// position k has its LSE at lse[k] + r * lse_stride and its four dims at byte offset off[k] + r * o_stride
+// of the buffer resource `rows`.  All LSE values and all O pieces of the tile are requested before anything
+// is used: one memory round trip per tile, whatever the weights turn out to be (these merges are chains of
+// such trips, and their number is what they cost).  Loads are device-scope ones, which is what the chunk
+// rows need and does no harm to the others.  A row of weight zero (LSE = -inf) is fetched like the others
+// but never enters the sums, so whatever its O holds (it may never have been written) does no harm.
+__device__ __forceinline__ void merge_tile(RowAcc (&a)[kMergeLanes], const bool (&on)[kMergeLanes], int n,
+                                           const float* const (&lse)[kMergeLanes], long long lse_stride,
+                                           __amdgpu_buffer_rsrc_t rows, const int (&off)[kMergeLanes], int o_stride)
 {
-    const bool final_row = mode == kRowFinal || mode == kRowFinalFold;
+    constexpr int kDeviceScope = 1 << 4;
+    float l[kMergeLanes][kMergeTile];
+    f32x4 x[kMergeLanes][kMergeTile];
+#pragma unroll
+    for (int k = 0; k < kMergeLanes; ++k)
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u)
+            l[k][u] = (on[k] && u < n) ? __hip_atomic_load(lse[k] + u * lse_stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                       : -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kMergeLanes; ++k)
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) {
+            x[k][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (on[k] && u < n)
+                x[k][u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rows, off[k] + u * o_stride, 0, kDeviceScope));
+        }
+#pragma unroll
+    for (int k = 0; k < kMergeLanes; ++k) {
+        float m_new = a[k].m;
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) m_new = fmaxf(m_new, l[k][u]);
+        // (nothing live so far: m_new = -inf, every weight below is zero and the state stays as it is)
+        const float keep = a[k].m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((a[k].m - m_new) * kLog2e);
+        a[k].acc *= keep;
+        a[k].wsum *= keep;
+        a[k].m = m_new;
+#pragma unroll
+        for (int u = 0; u < kMergeTile; ++u) {
+            const bool live = l[k][u] != -INFINITY;
+            const float w = live ? __builtin_amdgcn_exp2f((l[k][u] - m_new) * kLog2e) : 0.f;
+            a[k].wsum += w;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) a[k].acc[c] += live ? w * x[k][u][c] : 0.f;
+        }
+    }
+}
+
+// a pointer that is the same in all lanes, said so to the compiler (arguments of an out-of-line function
+// arrive in vector registers)
+__device__ __forceinline__ const float* uniform_ptr(const float* ptr)
+{
+    const unsigned long long t = reinterpret_cast<unsigned long long>(ptr);
+    const unsigned lo = (unsigned)uniform((int)(unsigned)t), hi = (unsigned)uniform((int)(unsigned)(t >> 32));
+    return reinterpret_cast<const float*>(((unsigned long long)hi << 32) | (unsigned long long)lo);
+}
+
+// rows of one sequence in a source are addressed through a buffer resource with 32-bit offsets: at most
+// this many bytes of them are merged (2 GiB: more rows than any batch holds)
+constexpr long long kMergeSpanBytes = 0x7fffffffLL;
+
+// (jobs sit in LDS and the persistent kernel has exactly one call of this routine, in a loop over the jobs
+// of a ticket: inlined several times, its unrolled tiles tripled the kernel's size and pushed scalar
+// registers of the streaming loop into spills; as a real call it would need scratch memory)
+__device__ __forceinline__ void merge_and_store_final(const MergeJob* job, int lane)
+{
+    const MergeJob& j = *job;
+    void* const out_o = const_cast<float*>(uniform_ptr(static_cast<const float*>(j.out_o)));
+    float* const out_lse_ptr = const_cast<float*>(uniform_ptr(j.out_lse));
+    const bool out_bf16 = uniform(j.out_bf16) != 0;
+    const int hq = uniform(j.hq), seq = uniform(j.seq), head0 = uniform(j.head0), heads = uniform(j.heads);
+    const int n_chunks = uniform(j.n_chunks), n_ext = uniform(j.n_ext), max_chunks = uniform(j.max_chunks);
+    const long long orow0 = (long long)seq * hq + head0;
+    const long long prow0 = (long long)seq * max_chunks * hq + head0;
+    const int row_bytes = hq * kD * 4;                                   // between consecutive rows of a source
+    for (int base = lane; base < heads * (kD / 4); base += kWave * kMergeLanes) {
+        RowAcc a[kMergeLanes];
+        bool on[kMergeLanes];
+        int g[kMergeLanes], d[kMergeLanes], off[kMergeLanes];
+        const float* lse[kMergeLanes];
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            const int idx = base + k * kWave;
+            on[k] = idx < heads * (kD / 4);
+            g[k] = on[k] ? idx >> 5 : 0;
+            d[k] = (idx & 31) * 4;
+            off[k] = (g[k] * kD + d[k]) * 4;
+            f32x4 own = {0.f, 0.f, 0.f, 0.f};
+            float own_lse = -INFINITY;
+            if (j.own_lds && on[k]) combine_quad(j.own_lds, uniform(j.group), idx, uniform(j.w0), uniform(j.w1), own, own_lse);
+            a[k].m = own_lse;
+            a[k].wsum = own_lse == -INFINITY ? 0.f : 1.f;
+            a[k].acc = own;
+        }
+        // the sequence's chunk rows, in chunk order
+        if (n_chunks > 0) {
+            const float* rows = uniform_ptr(j.part_o) + prow0 * kD;
+            const long long span = (long long)n_chunks * row_bytes;
+            const __amdgpu_buffer_rsrc_t rs = byte_buffer(rows, (int)(span < kMergeSpanBytes ? span : kMergeSpanBytes));
+            for (int c = 0; c < n_chunks; c += kMergeTile) {
+                int at[kMergeLanes];
+#pragma unroll
+                for (int k = 0; k < kMergeLanes; ++k) {
+                    lse[k] = j.part_lse + prow0 + g[k] + (long long)c * hq;
+                    at[k] = off[k] + c * row_bytes;
+                }
+                merge_tile(a, on, min(kMergeTile, n_chunks - c), lse, hq, rs, at, row_bytes);
+            }
+        }
+        // the rows computed elsewhere, source by source
+        for (int s = 0; s < n_ext; ++s) {
+            const int r0 = uniform(j.r0[s]), r1 = uniform(j.r1[s]);
+            if (r1 <= r0) continue;
+            const float* rows = uniform_ptr(j.ext_o[s]) + ((long long)r0 * hq + head0) * kD;
+            const long long span = (long long)(r1 - r0) * row_bytes;
+            const __amdgpu_buffer_rsrc_t rs = byte_buffer(rows, (int)(span < kMergeSpanBytes ? span : kMergeSpanBytes));
+            for (int r = r0; r < r1; r += kMergeTile) {
+                int at[kMergeLanes];
+#pragma unroll
+                for (int k = 0; k < kMergeLanes; ++k) {
+                    lse[k] = j.ext_lse[s] + (long long)r * hq + head0 + g[k];
+                    at[k] = off[k] + (r - r0) * row_bytes;
+                }
+                merge_tile(a, on, min(kMergeTile, r1 - r), lse, hq, rs, at, row_bytes);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kMergeLanes; ++k) {
+            f32x4 out = {0.f, 0.f, 0.f, 0.f};
+            float out_lse = -INFINITY;
+            if (a[k].m != -INFINITY) {
+                out = a[k].acc * (1.f / a[k].wsum);
+                out_lse = a[k].m + __builtin_amdgcn_logf(a[k].wsum) * kLn2;
+            }
+            if (on[k]) store_final_quad(out_o, out_lse_ptr, out_bf16, orow0 + g[k], d[k], out, out_lse);
+        }
+    }
+}
+
+// Final rows of a sequence that has no resident token at all: whatever the other sources hold for it, one
+// row at a time (rare, and kept small: this sits in the writer wave's prologue).
+__device__ __forceinline__ void fold_rows_plain(const DecodeParams& p, int seq, int lane)
+{
+    for (int idx = lane; idx < p.hq * (kD / 4); idx += kWave) {
+        const int head = idx >> 5, d = (idx & 31) * 4;
+        float m = -INFINITY, wsum = 0.f;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < p.n_ext; ++s) {
+            int r0, r1;
+            src_rows(p.ext[s], seq, r0, r1);
+            for (int r = r0; r < r1; ++r) {
+                const float l = p.ext[s].lse[(long long)r * p.hq + head];
+                if (l == -INFINITY) continue;
+                const f32x4 x = *reinterpret_cast<const f32x4*>(p.ext[s].o + ((long long)r * p.hq + head) * kD + d);
+                const float m_new = fmaxf(m, l);
+                const float keep = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m - m_new) * kLog2e);
+                const float w = __builtin_amdgcn_exp2f((l - m_new) * kLog2e);
+                acc = acc * keep + w * x;
+                wsum = wsum * keep + w;
+                m = m_new;
+            }
+        }
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        float lse = -INFINITY;
+        if (m != -INFINITY) {
+            o = acc * (1.f / wsum);
+            lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+        }
+        store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, (long long)seq * p.hq + head, d, o, lse);
+    }
+}
+
+// a job for rows [head0, head0 + heads) of `seq`: outputs and the rows other sources hold for the sequence;
+// written by one wave into its slot in LDS (every lane stores the same values)
+__device__ __forceinline__ void merge_job(MergeJob& j, const DecodeParams& p, int seq, int head0, int heads)
+{
+    j.out_o = p.out_o; j.out_lse = p.out_lse; j.part_o = p.part_o; j.part_lse = p.part_lse;
+    j.hq = p.hq; j.max_chunks = p.max_chunks; j.out_bf16 = p.out_bf16; j.n_ext = p.n_ext;
+    j.seq = seq; j.head0 = head0; j.heads = heads; j.group = p.group;
+    j.own_lds = nullptr; j.w0 = 0; j.w1 = 0; j.n_chunks = 0;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        j.ext_o[s] = p.ext[s].o;
+        j.ext_lse[s] = p.ext[s].lse;
+        j.r0[s] = j.r1[s] = 0;
+        if (s < p.n_ext) {
+            src_rows(p.ext[s], seq, j.r0[s], j.r1[s]);
+            const long long most = kMergeSpanBytes / ((long long)p.hq * kD * 4);      // rows a resource can span
+            if ((long long)j.r1[s] - j.r0[s] > most) j.r1[s] = j.r0[s] + (int)most;
+        }
+    }
+}
+
+// after a barrier: the item's rows from the states of waves w0 .. w1-1, and their stores (only seq, chunk and
+// kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn.  The fold of rows
+// from other sources is the out-of-line merge's (one wave calls this then).
+template <bool can_fold>
+__device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
+                                                  int tid, int nthreads, int mode, MergeJob* job = nullptr,
+                                                  int w0 = 0, int w1 = kWaves)
+{
+    if (can_fold && mode == kRowFinalFold) {           // left to the merge routine: the caller runs the job
+        merge_job(*job, p, it.seq, it.kvh * G, G);
+        job->own_lds = lds; job->w0 = w0; job->w1 = w1;
+        return;
+    }
+    const bool final_row = mode == kRowFinal;
     // a final row is also kept as a partial one when the call has a single chunk slot and a partial buffer
     const bool partial_row = !final_row || p.max_chunks == 1;
-    const long long prow0 = ((long long)it.seq * p.max_chunks + it.chunk) * p.hq + (long long)it.kvh * G;
+    const long long prow0 = ((long long)it.seq * p.max_chunks + chunk_index(it.chunk)) * p.hq + (long long)it.kvh * G;
     const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
-    auto store_partial = [&](int g, int d, f32x4 o, float lse) {
+    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
+        const int g = idx >> 5, d = (idx & 31) * 4;
+        f32x4 o;
+        float lse;
+        combine_quad(lds, G, idx, w0, w1, o, lse);
         if (p.part_o && partial_row && lse != -INFINITY) {
             if (mode == kRowShared) store_shared4(p.part_o + prow0 * kD, G * kD * 4, (g * kD + d) * 4, o);
             else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
@@ -738,86 +832,24 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             if (mode == kRowShared) __hip_atomic_store(p.part_lse + prow0 + g, lse, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             else p.part_lse[prow0 + g] = partial_row ? lse : -INFINITY;
         }
-    };
-    if (mode != kRowFinalFold) {
-        for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
-            const int g = idx >> 5, d = (idx & 31) * 4;
-            f32x4 o;
-            float lse;
-            combine_quad(lds, G, idx, w0, w1, o, lse);
-            store_partial(g, d, o, lse);
-            if (final_row) store_final_quad(p, orow0 + g, d, o, lse);
-        }
-        return;
-    }
-    // the final row after folding in what other sources hold for the sequence
-    int r0[3], r1[3];
-    ext_row_ranges(p, it.seq, r0, r1);
-    for (int base = tid; base < G * (kD / 4); base += nthreads * kMergeLanes) {
-        RowAcc a[kMergeLanes];
-        bool on[kMergeLanes];
-        int g[kMergeLanes], d[kMergeLanes], head[kMergeLanes];
-#pragma unroll
-        for (int k = 0; k < kMergeLanes; ++k) {
-            const int idx = base + k * nthreads;
-            on[k] = idx < G * (kD / 4);
-            g[k] = on[k] ? idx >> 5 : 0;
-            d[k] = (idx & 31) * 4;
-            head[k] = it.kvh * G + g[k];
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-            float lse = -INFINITY;
-            if (on[k]) {
-                combine_quad(lds, G, idx, w0, w1, o, lse);
-                store_partial(g[k], d[k], o, lse);
-            }
-            a[k].start(o, lse);
-        }
-        fold_ext_rows(p, r0, r1, a, on, head, d);
-#pragma unroll
-        for (int k = 0; k < kMergeLanes; ++k) {
-            if (!on[k]) continue;
-            f32x4 o;
-            float lse;
-            a[k].finish(o, lse);
-            store_final_quad(p, orow0 + g[k], d[k], o, lse);
-        }
+        if (final_row) store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + g, d, o, lse);
     }
 }
 
 // rows of an empty range: LSE = -inf, partial O left unwritten; `heads` rows from `head0`.  `final_here`:
-// the range is the sequence's whole (empty) range and the call writes final rows: O = 0 and LSE = -inf, or
-// whatever the other sources hold for the sequence.
+// the range is the sequence's whole (empty) range and the call writes final rows: O = 0 and LSE = -inf
+// (what other sources hold for such a sequence is the out-of-line merge's, see the persistent form).
 __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int chunk, int head0, int heads,
                                             int tid, int nthreads, bool final_here)
 {
     const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + head0;
+    const long long orow0 = (long long)seq * p.hq + head0;
     if (p.part_lse)
         for (int h = tid; h < heads; h += nthreads) p.part_lse[prow0 + h] = -INFINITY;
     if (final_here) {
-        int r0[3], r1[3];
-        ext_row_ranges(p, seq, r0, r1);
-        for (int base = tid; base < heads * (kD / 4); base += nthreads * kMergeLanes) {
-            RowAcc a[kMergeLanes];
-            bool on[kMergeLanes];
-            int d[kMergeLanes], head[kMergeLanes];
-#pragma unroll
-            for (int k = 0; k < kMergeLanes; ++k) {
-                const int idx = base + k * nthreads;
-                on[k] = idx < heads * (kD / 4);
-                head[k] = head0 + (on[k] ? idx >> 5 : 0);
-                d[k] = (idx & 31) * 4;
-                a[k].start(f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
-            }
-            if (p.n_ext > 0) fold_ext_rows(p, r0, r1, a, on, head, d);
-#pragma unroll
-            for (int k = 0; k < kMergeLanes; ++k) {
-                if (!on[k]) continue;
-                f32x4 o;
-                float lse;
-                a[k].finish(o, lse);
-                store_final_quad(p, (long long)seq * p.hq + head[k], d[k], o, lse);
-            }
-        }
+        for (int idx = tid; idx < heads * (kD / 4); idx += nthreads)
+            store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + (idx >> 5), (idx & 31) * 4,
+                             f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
     }
 }
 
@@ -834,16 +866,17 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     const int item = blockIdx.x;
     it.kvh = item % p.hkv;
     it.seq = (item / p.hkv) % p.batch;
-    it.chunk = item / (p.hkv * p.batch);
+    const int chunk = item / (p.hkv * p.batch);
     int b, e;
     seq_range(p, it.seq, b, e);
-    chunk_range(p, b, e, it.chunk, it.cb, it.ce);
-    it.n_live = live_chunks(p, b, e);
-    if (p.seq_final && it.chunk == 0 && it.kvh == 0 && threadIdx.x == 0)
-        p.seq_final[it.seq] = (p.out_o != nullptr && it.n_live <= 1) ? 1 : 0;
+    chunk_range(p, b, e, chunk, it.cb, it.ce);
+    const int n_live = live_chunks(p, b, e);
+    it.chunk = pack_chunk(chunk, n_live);
+    if (p.seq_final && chunk == 0 && it.kvh == 0 && threadIdx.x == 0)
+        p.seq_final[it.seq] = (p.out_o != nullptr && n_live <= 1) ? 1 : 0;
     if (it.ce <= it.cb) {
-        store_empty(p, it.seq, it.chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads,
-                    p.out_o != nullptr && it.chunk == 0);
+        store_empty(p, it.seq, chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads,
+                    p.out_o != nullptr && chunk == 0);
         return;
     }
     finish_item(it, block_table, p.max_blocks);
@@ -865,7 +898,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     __syncthreads();
     stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
     __syncthreads();
-    combine_and_store(p, it, lds, p.group, threadIdx.x, kThreads, row_mode(p, it.n_live));
+    combine_and_store<false>(p, it, lds, p.group, threadIdx.x, kThreads, row_mode(p, n_live));
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1006,7 +1039,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         const bool live = ce > cb;
         const unsigned slot = wave_take_slot(hist, live ? sort_bin(ce - cb, bins_per_page) : kSortBins, e < total,
                                              full_bin, kSortBins);
-        if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, (int)((unsigned)chunk | ((unsigned)n_live << 16)), cb, ce};
+        if (e < total) entries[live ? slot : (unsigned)(total - 1) - slot] = WorkEntry{seq, pack_chunk(chunk, n_live), cb, ce};
     }
 }
 
@@ -1044,19 +1077,8 @@ __host__ __device__ __forceinline__ bool ticket_index(const TicketSpace& ts, uns
     return idx < ts.n_items;
 }
 
-// Where a launch finds its work list: in the workspace (written by decode_list_kernel), or in the
-// workgroup's own LDS (built by every workgroup for itself at the start of the launch, see build_list_lds).
-struct ListView {
-    bool in_lds;
-    const WorkEntry* entries;          // workspace list: non-empty entries from the front, empty ones from the back
-    const unsigned* lds_entry;         // LDS list: sequence << 16 | chunk; non-empty entries first, then the empty ones
-    const int* lds_b;                  // LDS list: clamped range of every sequence
-    const int* lds_e;
-    unsigned n_live, n_empty, n_long;  // non-empty entries, empty entries, non-empty entries longer than kShortTokens
-};
-
 // this wave's item under a ticket (ticket < n_tickets); n_steps = 0 if the wave has none
-__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const ListView& lv,
+__device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEntry* __restrict__ entries,
                                             const int* __restrict__ block_table, const TicketSpace& ts,
                                             unsigned ticket, int wave)
 {
@@ -1064,29 +1086,17 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const ListVie
     unsigned idx;
     const bool valid = ticket_index(ts, ticket, wave, idx, grouped);
     idx = valid ? idx : ts.n_items - 1u;
+    const WorkEntry w = load_invariant(entries + idx / (unsigned)p.hkv);
     Item it;
     it.kvh = (int)(idx % (unsigned)p.hkv);
-    if (lv.in_lds) {
-        // (read with instructions of their own, like the ticket slots: see lds_peek)
-        const unsigned packed = (unsigned)uniform((int)lds_peek(lv.lds_entry + idx / (unsigned)p.hkv));
-        it.seq = (int)(packed >> 16);
-        it.chunk = (int)(packed & 0xffffu);
-        const int b = uniform((int)lds_peek(reinterpret_cast<const unsigned*>(lv.lds_b + it.seq)));
-        const int e = uniform((int)lds_peek(reinterpret_cast<const unsigned*>(lv.lds_e + it.seq)));
-        chunk_range(p, b, e, it.chunk, it.cb, it.ce);
-        it.n_live = live_chunks(p, b, e);
-    } else {
-        const WorkEntry w = load_invariant(lv.entries + idx / (unsigned)p.hkv);
-        // A list that was planned for these very ranges holds only values that pass unchanged; one reused
-        // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are
-        // the worst that can come of it, never an access outside the table or the output buffers.
-        const int cap = p.max_blocks * kBlockSize;
-        it.seq = min(max(w.seq, 0), p.batch - 1);
-        it.chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
-        it.n_live = min(max((int)((unsigned)w.chunk >> 16), 1), p.max_chunks);
-        it.cb = min(max(w.cb, 0), cap - 1);
-        it.ce = min(max(w.ce, it.cb + 1), cap);
-    }
+    // A list that was planned for these very ranges holds only values that pass unchanged; one reused
+    // against the contract (other batch, other chunking) is forced into bounds, so that wrong rows are the
+    // worst that can come of it, never an access outside the table or the output buffers.
+    const int cap = p.max_blocks * kBlockSize;
+    it.seq = min(max(w.seq, 0), p.batch - 1);
+    it.chunk = pack_chunk(min(chunk_index(w.chunk), p.max_chunks - 1), min(max(chunk_live(w.chunk), 1), p.max_chunks));
+    it.cb = min(max(w.cb, 0), cap - 1);
+    it.ce = min(max(w.ce, it.cb + 1), cap);
     finish_item(it, block_table, p.max_blocks);
     it.s0 = grouped ? 0 : wave;
     it.ds = grouped ? 1 : kWaves;
@@ -1094,114 +1104,11 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const ListVie
     return it;
 }
 
-// ---- the work list built inside the attention launch ---------------------------------------------------
-// When the list is small enough, every workgroup builds it for itself in LDS at the start of the launch
-// instead of reading one that a launch of its own wrote to the workspace: the same longest-first counting
-// sort, but stable (an entry's place among the entries of its sort bin is its index order), so that all
-// workgroups arrive at the identical list without talking to each other.  What it saves is the list
-// kernel and the gap between the two launches (about 7 us per step), and one trip to memory at every
-// hand-over (the next item's entry now comes from LDS).
-// LDS layout (32-bit words): 8 header words (non-empty entries, empty entries, long entries), the clamped
-// ranges b[batch] and e[batch], kListWaves x (kSortBins + 1) counters, then the entries.
-constexpr int kListWaves = kPersistentThreads / kWave;
-constexpr int kListHeaderWords = 8;
-constexpr int kListMaxEntries = 8192;
-constexpr int kListMaxBatch = 4096;
-
-__host__ __device__ __forceinline__ size_t list_lds_bytes(long long batch, long long max_chunks)
-{
-    return (size_t)(kListHeaderWords + 2 * batch + kListWaves * (kSortBins + 1) + batch * max_chunks) * 4;
-}
-
-// all kPersistentThreads threads of the workgroup; ends with a barrier
-__device__ __forceinline__ ListView build_list_lds(const DecodeParams& p, unsigned* area)
-{
-    unsigned* hdr = area;
-    int* lb = reinterpret_cast<int*>(area + kListHeaderWords);
-    int* le = lb + p.batch;
-    unsigned* hist = reinterpret_cast<unsigned*>(le + p.batch);
-    unsigned* ent = hist + kListWaves * (kSortBins + 1);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int total = p.batch * p.max_chunks;
-    const float bins_per_page = sort_bins_per_page(p.chunk_tokens);
-    for (int i = tid; i < p.batch; i += kPersistentThreads) {
-        int b, e;
-        seq_range(p, i, b, e);
-        lb[i] = b;
-        le[i] = e;
-    }
-    for (int i = tid; i < kListWaves * (kSortBins + 1); i += kPersistentThreads) hist[i] = 0;
-    __syncthreads();
-    // every wave takes a contiguous block of entries (whole rounds of 64), in index order
-    const int per = (((total + kListWaves - 1) / kListWaves) + kWave - 1) / kWave * kWave;
-    const int first = wave * per, last = min(total, first + per);
-    unsigned* my_hist = hist + wave * (kSortBins + 1);
-    auto key_of = [&](int e, unsigned& packed) {
-        const int seq = e / p.max_chunks, chunk = e - seq * p.max_chunks;
-        int cb, ce;
-        chunk_range(p, lb[seq], le[seq], chunk, cb, ce);
-        packed = ((unsigned)seq << 16) | (unsigned)chunk;
-        return ce > cb ? sort_bin(ce - cb, bins_per_page) : kSortBins;
-    };
-    for (int e = first + lane; e < last; e += kWave) {
-        unsigned packed;
-        atomicAdd(&my_hist[key_of(e, packed)], 1u);
-    }
-    __syncthreads();
-    if (wave == 0) {
-        // exclusive scan over (bin, wave) in that order: where each wave's entries of each bin start
-        constexpr int kCount = kListWaves * (kSortBins + 1);
-        constexpr int kPer = (kCount + kWave - 1) / kWave;
-        unsigned c[kPer], sum = 0;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const int j = lane * kPer + i;
-            c[i] = j < kCount ? hist[(j % kListWaves) * (kSortBins + 1) + j / kListWaves] : 0u;
-            sum += c[i];
-        }
-        unsigned incl = sum;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const unsigned up = __shfl_up(incl, d);
-            if (lane >= d) incl += up;
-        }
-        unsigned run = incl - sum;
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const int j = lane * kPer + i;
-            if (j < kCount) {
-                if (j == kSortBins * kListWaves) { hdr[0] = run; hdr[1] = (unsigned)total - run; }
-                if (j == kLongBins * kListWaves) hdr[2] = run;
-                hist[(j % kListWaves) * (kSortBins + 1) + j / kListWaves] = run;
-            }
-            run += c[i];
-        }
-    }
-    __syncthreads();
-    // an entry's slot: its wave's running counter of its bin; lanes of one round that share a bin are
-    // served in lane order, rounds follow each other in program order
-    for (int e = first + lane; e < last; e += kWave) {
-        unsigned packed;
-        const int key = key_of(e, packed);
-        const unsigned slot = atomicAdd(&my_hist[key], 1u);
-        ent[slot] = packed;
-    }
-    __syncthreads();
-    ListView lv;
-    lv.in_lds = true;
-    lv.entries = nullptr;
-    lv.lds_entry = ent;
-    lv.lds_b = lb;
-    lv.lds_e = le;
-    lv.n_live = (unsigned)uniform((int)hdr[0]);
-    lv.n_empty = (unsigned)uniform((int)hdr[1]);
-    lv.n_long = (unsigned)uniform((int)hdr[2]);
-    return lv;
-}
-
 constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming waves tell the writer about an item
 
-// `entries` == nullptr: the list is built in LDS by the workgroup itself
+// `fused`: the launch may finish sequences by merging (p.fuse); the plain instance carries none of that code,
+// whose register needs change how the compiler schedules the streaming loop (2 % of the launch).
+template <bool fused>
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
@@ -1211,44 +1118,29 @@ __device__ __forceinline__ void persistent_body(
     // by ticket parity: [0] 1 if the workgroup's last, [1] 1 if one item per wave, then (seq, chunk, kvh,
     // non-empty chunks of the sequence) of the item (slot 0) or of each wave's item (seq < 0: the wave had none)
     __shared__ int sh_item[2][kItemWords];
+    __shared__ MergeJob sh_job[kWaves];                    // the writer wave's jobs for the merge routine, per ticket
     const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by ticket parity
     char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
     char* const q_base = stage_base + kWaves * kStageBytes;          // [parity][wave] buffers of G rows
     const int q_bytes = p.group * kD * 2;
     const LaneIds id(stage_base);
-    ListView lv;
-    if (entries == nullptr) {
-        lv = build_list_lds(p, reinterpret_cast<unsigned*>(q_base + 2 * kWaves * q_bytes));
-    } else {
-        const unsigned total = (unsigned)(p.batch * p.max_chunks);
-        lv.in_lds = false;
-        lv.entries = entries;
-        lv.lds_entry = nullptr;
-        lv.lds_b = lv.lds_e = nullptr;
-        lv.n_live = min(counts[0], total);
-        lv.n_empty = min(counts[1], total);
-        lv.n_long = counts[5];
-    }
-    const TicketSpace ts = make_ticket_space(lv.n_live, lv.n_long, (unsigned)p.hkv, gridDim.x);
+    const unsigned total = (unsigned)(p.batch * p.max_chunks);
+    const TicketSpace ts = make_ticket_space(min(counts[0], total), counts[5], (unsigned)p.hkv, gridDim.x);
     const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
 
     // rows of empty chunks: LSE = -inf, and the final row of a sequence whose whole range is empty (stores
     // only, shared out over the resident workgroups); and which sequences this call finishes
     auto store_empty_share = [&] {
-        const unsigned last = (unsigned)(p.batch * p.max_chunks) - 1u;
-        for (unsigned i = blockIdx.x; i < lv.n_empty; i += gridDim.x) {
-            int seq, chunk;
-            if (lv.in_lds) {
-                const unsigned packed = lv.lds_entry[lv.n_live + i];
-                seq = (int)(packed >> 16);
-                chunk = (int)(packed & 0xffffu);
-            } else {
-                const WorkEntry w = load_invariant(entries + (last - i));
-                seq = min(max(w.seq, 0), p.batch - 1);
-                chunk = min(w.chunk & 0xffff, p.max_chunks - 1);
-            }
-            store_empty(p, uniform(seq), uniform(chunk), 0, p.hq, id.lane, kWave, p.out_o != nullptr && chunk == 0);
+        auto empty_slot = [&](int seq, int chunk) {
+            const bool final_here = p.out_o != nullptr && chunk == 0;
+            store_empty(p, seq, chunk, 0, p.hq, id.lane, kWave, final_here && !(fused && p.n_ext > 0));
+            if (fused && final_here && p.n_ext > 0) fold_rows_plain(p, seq, id.lane);
+        };
+        const unsigned n_empty = min(counts[1], total);
+        for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
+            const WorkEntry w = load_invariant(entries + (total - 1u - i));
+            empty_slot(uniform(min(max(w.seq, 0), p.batch - 1)), uniform(min(chunk_index(w.chunk), p.max_chunks - 1)));
         }
         if (p.seq_final) {
             for (int i = blockIdx.x * kWave + id.lane; i < p.batch; i += gridDim.x * kWave) {
@@ -1282,10 +1174,8 @@ __device__ __forceinline__ void persistent_body(
     };
     unsigned tk = blockIdx.x;
     const bool writer = id.wave == kWaves;                 // the fifth wave
-    if (tk >= n_tickets) {
-        if (writer) store_empty_share();
-        return;
-    }
+    if (writer) store_empty_share();
+    if (tk >= n_tickets) return;
 
     // The writer wave does every global store of the workgroup: the rows of empty chunks now, then, ticket
     // after ticket, the combine of the four streaming waves' states and the rows of the item (or of the
@@ -1300,27 +1190,31 @@ __device__ __forceinline__ void persistent_body(
     // they go out as plain stores, which the L2 gathers (with the hint each is a partial-line write to
     // memory: 1-1.5 % of the launch on configs 3 and 5).
     if (writer) {
-        store_empty_share();
         lds_barrier();
         for (int k = 0;; ++k) {
             lds_barrier();                                 // ticket k is staged
             const int* si = sh_item[k & 1];
             const bool last = si[0] != 0, grouped = si[1] != 0;
             const float* area = reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes);
+            // An item's rows are stored at once, unless they still have to be merged with rows from
+            // elsewhere: those become jobs of the merge routine (at most one per item), run at the end.
             Item done;
             bool shared = false;
+            int n_jobs = 0;
             const int n_done = grouped ? kWaves : 1;
             for (int w = 0; w < n_done; ++w) {
                 done.seq = uniform(si[2 + 4 * w]);
                 done.chunk = uniform(si[3 + 4 * w]);
                 done.kvh = uniform(si[4 + 4 * w]);
                 if (done.seq < 0) continue;
-                const int mode = row_mode(p, uniform(si[5 + 4 * w]));
+                const int mode = row_mode(p, chunk_live(done.chunk));
                 shared |= mode == kRowShared;
-                if (grouped) combine_and_store(p, done, area, p.group, id.lane, kWave, mode, w, w + 1);
-                else combine_and_store(p, done, area, p.group, id.lane, kWave, mode);
+                MergeJob* job = &sh_job[n_jobs];
+                if (grouped) combine_and_store<fused>(p, done, area, p.group, id.lane, kWave, mode, job, w, w + 1);
+                else combine_and_store<fused>(p, done, area, p.group, id.lane, kWave, mode, job);
+                if (fused && mode == kRowFinalFold) ++n_jobs;
             }
-            if (shared) {
+            if (fused && shared) {
                 // The fused form.  The rows just stored (at device scope) have left this wave for good once
                 // its vector-memory counter is back to zero; only then does the item count as arrived.
                 // Whoever brings a (sequence, kv head)'s count to the number of its non-empty chunks finds
@@ -1328,19 +1222,24 @@ __device__ __forceinline__ void persistent_body(
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 OMNI_WAIT_VMCNT(0);
                 for (int w = 0; w < n_done; ++w) {
-                    const int seq = uniform(si[2 + 4 * w]), kvh = uniform(si[4 + 4 * w]), n_live = uniform(si[5 + 4 * w]);
+                    const int seq = uniform(si[2 + 4 * w]), kvh = uniform(si[4 + 4 * w]);
+                    const int n_live = chunk_live(uniform(si[3 + 4 * w]));
                     if (seq < 0 || row_mode(p, n_live) != kRowShared) continue;
                     unsigned* counter = arrivals + (long long)seq * p.hkv + kvh;
                     unsigned before = 0;
                     if (id.lane == 0) before = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     before = (unsigned)uniform((int)before);
                     if (before + 1u == (unsigned)n_live) {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        merge_chunks_and_store(p, seq, kvh, n_live, p.group, id.lane, kWave);
                         if (id.lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        merge_job(sh_job[n_jobs], p, seq, kvh * p.group, p.group);
+                        sh_job[n_jobs].n_chunks = n_live;
+                        ++n_jobs;
                     }
                 }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             }
+            if (fused)
+                for (int i = 0; i < n_jobs; ++i) merge_and_store_final(&sh_job[i], id.lane);
             if (last) break;
         }
         return;
@@ -1348,7 +1247,7 @@ __device__ __forceinline__ void persistent_body(
 
     // first ticket: Q goes into LDS, every wave requests its first step, then all read Q; the stores for
     // the empty rows go out while those first loads are on their way
-    Item it = ticket_item(p, lv, block_table, ts, tk, id.wave);
+    Item it = ticket_item(p, entries, block_table, ts, tk, id.wave);
     if (threadIdx.x == 0) {
         sh_ticket[0] = kPending;
         sh_ticket[2] = kPending;
@@ -1395,7 +1294,7 @@ __device__ __forceinline__ void persistent_body(
             if (tn == kPending) gave_up = true;
             has_next = tn < n_tickets;
             if (has_next) {
-                nx = ticket_item(p, lv, block_table, ts, tn, id.wave);
+                nx = ticket_item(p, entries, block_table, ts, tn, id.wave);
                 if (has_steps(nx)) tail = Tail{true, nx.kvh, step_pages(p, nx, nx.s0)};
                 // the table reads for the wave's second step of that item go out now as well: at the
                 // item's start they would be a cold round trip in front of its second request
@@ -1454,7 +1353,6 @@ __device__ __forceinline__ void persistent_body(
             si[2 + 4 * id.wave] = streamed ? it.seq : -1;
             si[3 + 4 * id.wave] = it.chunk;
             si[4 + 4 * id.wave] = it.kvh;
-            si[5 + 4 * id.wave] = it.n_live;
         }
         lds_barrier();
         if (!has_next) break;
@@ -1469,11 +1367,12 @@ __device__ __forceinline__ void persistent_body(
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
+template <bool fused>
 __global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
-    persistent_body(p, block_table, header, counts, entries, arrivals);
+    persistent_body<fused>(p, block_table, header, counts, entries, arrivals);
     if (threadIdx.x == 0) {
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
@@ -1490,16 +1389,6 @@ size_t lds_bytes(int group, bool persistent)
         return a > b ? a : b;
     }
     return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)kWaves * group * kD * 2;
-}
-
-// dynamic LDS a workgroup may ask for: the CU's 160 KiB less the kernel's static words
-constexpr size_t kMaxDynamicLds = 160 * 1024 - 512;
-
-// whether a launch can build its list in LDS (then after the persistent form's other areas)
-bool list_fits_lds(const DecodeParams& p)
-{
-    return p.batch <= kListMaxBatch && (long long)p.batch * p.max_chunks <= kListMaxEntries &&
-           lds_bytes(p.group, true) + list_lds_bytes(p.batch, p.max_chunks) <= kMaxDynamicLds;
 }
 
 }  // namespace
@@ -1567,16 +1456,19 @@ hipError_t device_facts(int& cus)
     DeviceFacts& f = facts[dev];
     if (!f.known) {
         f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const int lds_p = (int)kMaxDynamicLds, lds_g = (int)lds_bytes(16, false);
-        if (f.status == hipSuccess)
-            f.status = hipFuncSetAttribute((const void*)decode_mfma_persistent_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
+        const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
+        if (f.status == hipSuccess) {
+            const void* forms[2] = {(const void*)decode_mfma_persistent_kernel<false>,
+                                    (const void*)decode_mfma_persistent_kernel<true>};
+            for (int i = 0; i < 2 && f.status == hipSuccess; ++i)
+                f.status = hipFuncSetAttribute(forms[i], hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
+        }
         if (f.status == hipSuccess && lds_g > 64 * 1024)
             f.status = hipFuncSetAttribute((const void*)decode_mfma_grid_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_g);
         int per_cu = 0;
         if (f.status == hipSuccess)
-            f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel,
+            f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel<true>,
                                                                     kPersistentThreads, lds_p);
         if (f.status == hipSuccess && (per_cu < 1 || f.cus < 1)) f.status = hipErrorLaunchOutOfResources;
         f.known = true;
@@ -1604,11 +1496,6 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
         e = launch_decode_plan(p, workspace, s);
         if (e != hipSuccess) return e;
     }
-    // A workspace that is known to be in order (planned: its counters are at rest, as omni_decode_plan and
-    // every finished launch leave them) lets the launch build a small list by itself; otherwise the list
-    // kernel has just put both in place.
-    const bool self_list = planned && list_fits_lds(p);
-    const size_t lds_all = lds + (self_list ? list_lds_bytes(p.batch, p.max_chunks) : 0);
     // One workgroup per CU.  More would fit (three), but the memory system is saturated by four waves
     // per CU already, and a CU serves its oldest waves first: a second and third workgroup get a
     // fraction of the first one's bandwidth, start late and finish late, which costs more at both ends
@@ -1616,8 +1503,9 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
-    hipLaunchKernelGGL(decode_mfma_persistent_kernel, dim3(grid), dim3(kPersistentThreads), lds_all, s, p,
-                       p.block_table, header, header + 1, self_list ? nullptr : entries, arrivals);
+    auto kernel = p.fuse ? decode_mfma_persistent_kernel<true> : decode_mfma_persistent_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p, p.block_table, header, header + 1,
+                       entries, arrivals);
     return hipGetLastError();
 }
 

@@ -106,8 +106,9 @@ __device__ __forceinline__ void chunk_range(const DecodeParams& p, int b, int e,
 __device__ __forceinline__ int live_chunks(const DecodeParams& p, int b, int e)
 {
     if (e <= b) return 0;
-    const long long n = ((long long)(e - b) + p.chunk_tokens - 1) / p.chunk_tokens;
-    return n < p.max_chunks ? (int)n : p.max_chunks;
+    // (both terms are at most the table width, which the API keeps below 2^30: 32-bit arithmetic is exact)
+    const unsigned n = ((unsigned)(e - b) + (unsigned)p.chunk_tokens - 1u) / (unsigned)p.chunk_tokens;
+    return n < (unsigned)p.max_chunks ? (int)n : p.max_chunks;
 }
 
 // ---- launchers (each defined beside its kernel) ---------------------------

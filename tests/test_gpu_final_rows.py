@@ -10,7 +10,7 @@ torch = pytest.importorskip("torch")
 from oracle import oracle
 from paper_2603_12831_amd import binding, workloads as wl
 from paper_2603_12831_amd.runner import DeviceWorkload
-from test_gpu_parity import (BENCH_FORM, KERNELS, REBUILT_LIST, THREADS, TOL, check, expected_full,
+from test_gpu_parity import (BENCH_FORM, KERNELS, PLANNED_LIST, THREADS, TOL, check, expected_full,
                              ext_partials_from_oracle)
 
 pytestmark = pytest.mark.gpu
@@ -112,7 +112,7 @@ def test_fused_form_finishes_every_sequence(out_dtype, shape):
     exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
     tol = TOL["bf16"] + (float(np.max(np.abs(exp[0]))) * 2.0 ** -9 if out_dtype == "bf16" else 0.0)
     o_m, l_m, _ = run_mode(w, "merge", out_dtype=out_dtype)
-    o_r, l_r, _ = run_mode(w, "fused", REBUILT_LIST, out_dtype=out_dtype, passes=2)
+    o_r, l_r, _ = run_mode(w, "fused", PLANNED_LIST, out_dtype=out_dtype, passes=2)
     o_f, l_f, dw = run_mode(w, "fused", out_dtype=out_dtype, passes=3)
     assert np.all(dw.seq_final.cpu().numpy() == 1)
     assert np.array_equal(o_r, o_f) and np.array_equal(l_r, l_f)

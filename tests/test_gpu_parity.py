@@ -25,14 +25,13 @@ TOL = {"f32": 1e-5, "bf16": 2e-3}
 THREADS = 16
 # (kernel selector, give a workspace): the vector kernel, and both launch forms of the automatic choice
 # (which is the matrix-core kernel for bf16 / head_dim 128 and the vector kernel otherwise)
-# the third form is a workspace prepared once (omni_decode_plan) and passed as planned: the persistent kernel
-# then builds its work list inside the attention launch when the list is small enough
+# the last form is a workspace prepared once (omni_decode_plan) and passed as planned to every call
 KERNELS = [pytest.param((binding.OMNI_KERNEL_VECTOR, False), id="vector"),
            pytest.param((binding.OMNI_KERNEL_AUTO, False), id="auto-grid"),
            pytest.param((binding.OMNI_KERNEL_AUTO, True), id="auto-persistent"),
            pytest.param((binding.OMNI_KERNEL_AUTO, 2), id="auto-persistent-planned")]
-BENCH_FORM = (binding.OMNI_KERNEL_AUTO, 2)             # what bench.py times
-REBUILT_LIST = (binding.OMNI_KERNEL_AUTO, True)        # the same kernel with the list kernel in front of every call
+BENCH_FORM = (binding.OMNI_KERNEL_AUTO, True)          # what bench.py times: the list is rebuilt by every step
+PLANNED_LIST = (binding.OMNI_KERNEL_AUTO, 2)           # the same kernel on a list built once
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -336,7 +335,7 @@ def test_work_list_with_many_sequences():
     w = wl.make_generic(62, np.maximum(lengths, 1), 4, 1, 128, dtype="bf16", chunk_tokens=32)
     w.calls[0].ctx_end = lengths.astype(np.int32)
     run_and_check(w, BENCH_FORM)
-    run_and_check(w, REBUILT_LIST)
+    run_and_check(w, PLANNED_LIST)
     run_and_check(w, (binding.OMNI_KERNEL_AUTO, False))
 
 
@@ -409,7 +408,7 @@ def test_seeded_random_batches(case):
         longest = int((lengths + begin).max())
         w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, (longest + chunk - 1) // chunk + int(rng.integers(0, 2))
     exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
-    for form in (BENCH_FORM, REBUILT_LIST):
+    for form in (BENCH_FORM, PLANNED_LIST):
         (_, _), dw = run_and_check(w, form, expected=exp)
         dw.poison_outputs()
         dw.run(kernel=form[0])
@@ -563,9 +562,9 @@ def test_full_cfg3():
     exp_o, _ = expected_full(w)
     dwb = DeviceWorkload(w, out_dtype="bf16")
     dwb.run()
-    # the grid form and the rebuilt-list form on the full size too
+    # the grid form and the planned-list form on the full size too
     run_and_check(w, (binding.OMNI_KERNEL_AUTO, False), out_dtype="f32")
-    run_and_check(w, REBUILT_LIST, out_dtype="f32")
+    run_and_check(w, PLANNED_LIST, out_dtype="f32")
     ob, _ = dwb.results()
     assert np.max(np.abs(ob - exp_o) / np.maximum(np.abs(exp_o), 2.0 ** -6)) <= 2.0 ** -8 + 1e-3
 
