@@ -200,6 +200,11 @@ omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_s
  * list and one arrival counter per (sequence, kv head) (0 if any of them is <= 0). */
 uint64_t omni_decode_workspace_bytes(int32_t batch, int32_t max_chunks, int32_t num_kv_heads);
 
+/* Name of the attention kernel omni_paged_decode_attn would launch for these arguments (a static string:
+ * "decode_mfma_persistent_kernel", "decode_mfma_grid_kernel" or "decode_vector_kernel"; "" if the call
+ * would be refused).  Host only, launches nothing: for measurement reports. */
+const char* omni_decode_kernel_name(const omni_decode_args* a);
+
 /*
  * Reads the diagnostic word of a workspace that holds a work list (see `workspace` above) into *count
  * (host memory) and puts it back to zero: the number of waves that gave a launch up since the list was
@@ -377,6 +382,10 @@ omni_status omni_debug_gather_kv(const omni_decode_args* a, int32_t seq, void* k
  */
 omni_status omni_debug_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+/* The host-side counterpart (HOST pointers, no GPU call): n_threads threads (0 = one per hardware thread)
+ * read `bytes` (multiple of 8) of host memory once, a contiguous slab each, folded into *sink: the
+ * streaming-read reference omni_host_partial_attn is compared with.  Returns when done. */
+omni_status omni_debug_host_stream_read(const void* src, size_t bytes, int32_t n_threads, uint64_t* sink);
 
 /*
  * Test aids for the persistent form's work list (host only, no GPU call; they run the functions the kernels

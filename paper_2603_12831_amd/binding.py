@@ -23,8 +23,9 @@ OMNI_ERR_TOO_LARGE = -6
 OMNI_STATIC_SCRATCH_BYTES = 2 * 1024 * 1024
 
 EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_decode_workspace_bytes", "omni_decode_plan",
-           "omni_decode_abandoned_waves", "omni_merge_partials", "omni_merge_partials_masked",
+           "omni_decode_abandoned_waves", "omni_decode_kernel_name", "omni_merge_partials", "omni_merge_partials_masked",
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
+           "omni_debug_host_stream_read",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
            "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
            "omni_host_partial_attn", "omni_debug_sort_bin", "omni_debug_ticket_map")
@@ -102,6 +103,8 @@ def load_library() -> ctypes.CDLL:
         lib.omni_decode_plan.restype = ctypes.c_int
         lib.omni_decode_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.omni_decode_workspace_bytes.restype = ctypes.c_uint64
+        lib.omni_decode_kernel_name.argtypes = [ctypes.POINTER(omni_decode_args)]
+        lib.omni_decode_kernel_name.restype = ctypes.c_char_p
         lib.omni_decode_abandoned_waves.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
         lib.omni_decode_abandoned_waves.restype = ctypes.c_int
         lib.omni_merge_partials_masked.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -120,6 +123,8 @@ def load_library() -> ctypes.CDLL:
         lib.omni_debug_stream_read.restype = ctypes.c_int
         lib.omni_debug_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.omni_debug_copy.restype = ctypes.c_int
+        lib.omni_debug_host_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64)]
+        lib.omni_debug_host_stream_read.restype = ctypes.c_int
         lib.omni_debug_sort_bin.argtypes = [ctypes.c_int32, ctypes.c_int32]
         lib.omni_debug_sort_bin.restype = ctypes.c_int32
         lib.omni_debug_ticket_map.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_uint32, vp,
@@ -267,6 +272,10 @@ def omni_decode_workspace_bytes(batch: int, max_chunks: int, num_kv_heads: int) 
     return int(load_library().omni_decode_workspace_bytes(int(batch), int(max_chunks), int(num_kv_heads)))
 
 
+def omni_decode_kernel_name(args: omni_decode_args) -> str:
+    return load_library().omni_decode_kernel_name(ctypes.byref(args)).decode()
+
+
 def omni_decode_abandoned_waves(workspace=None, stream=None) -> int:
     """Reads and clears the diagnostic word of a work list (None: the library's static scratch)."""
     n = ctypes.c_uint32(0)
@@ -353,6 +362,18 @@ def omni_debug_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> int:
     if st != OMNI_OK:
         raise OmniError(st, "omni_debug_copy")
     return st
+
+
+def omni_debug_host_stream_read(array, n_threads: int = 0) -> int:
+    """Reads a C-contiguous numpy array once with n_threads host threads; returns the fold of its words."""
+    nbytes = array.nbytes // 8 * 8
+    if not array.flags["C_CONTIGUOUS"]:
+        raise ValueError("array must be C-contiguous")
+    sink = ctypes.c_uint64(0)
+    st = load_library().omni_debug_host_stream_read(array.ctypes.data, nbytes, int(n_threads), ctypes.byref(sink))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_debug_host_stream_read")
+    return int(sink.value)
 
 
 def make_kv_cache(k_pool, v_pool, block_table=None) -> omni_kv_cache:

@@ -151,6 +151,18 @@ omni_status omni_paged_decode_attn_static(const omni_decode_args* a, void* hip_s
     return decode_attn(a, ws, OMNI_STATIC_SCRATCH_BYTES, false, hip_stream);
 }
 
+const char* omni_decode_kernel_name(const omni_decode_args* a)
+{
+    DecodeParams p;
+    if (flatten(a, p, true) != OMNI_OK) return "";
+    bool mfma = decode_mfma_supports(p, a->qkv_dtype == OMNI_BF16);
+    if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return "";
+    if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
+    if (!mfma) return (p.fuse || a->kernel > OMNI_KERNEL_MFMA || a->kernel < 0) ? "" : "decode_vector_kernel";
+    if (!a->workspace) return p.fuse ? "" : "decode_mfma_grid_kernel";
+    return "decode_mfma_persistent_kernel";
+}
+
 omni_status omni_decode_abandoned_waves(void* workspace, uint32_t* count, void* hip_stream)
 {
     if (!count) return OMNI_ERR_NULL;

@@ -263,3 +263,36 @@ extern "C" omni_status omni_host_partial_attn(const omni_host_attn_args* a)
     else produce<64>(p, n_threads);
     return OMNI_OK;
 }
+
+// Measurement aid: `n_threads` threads read `bytes` bytes of host memory once, each a contiguous slab, and
+// fold them into *sink (so that the reads cannot be dropped): what the host's memory gives threads that only
+// read - the streaming reference the producer above is set against.
+extern "C" omni_status omni_debug_host_stream_read(const void* src, size_t bytes, int32_t n_threads, uint64_t* sink)
+{
+    if (!src || !sink) return OMNI_ERR_NULL;
+    if (bytes % 8 != 0) return OMNI_ERR_SHAPE;
+    int n = n_threads > 0 ? n_threads : (int)std::max(1u, std::thread::hardware_concurrency());
+    const size_t words = bytes / 8;
+    const size_t per = (words + (size_t)n - 1) / (size_t)n;
+    std::vector<uint64_t> folds((size_t)n, 0);
+    auto worker = [&](int t) {
+        const uint64_t* w = static_cast<const uint64_t*>(src);
+        const size_t lo = std::min(words, (size_t)t * per), hi = std::min(words, lo + per);
+        uint64_t lanes[8] = {0, 0, 0, 0, 0, 0, 0, 0};              // eight running sums: vectorises as is
+        size_t i = lo;
+        for (; i + 8 <= hi; i += 8)
+            for (int j = 0; j < 8; ++j) lanes[j] += w[i + j];
+        for (; i < hi; ++i) lanes[0] += w[i];
+        uint64_t f = 0;
+        for (int j = 0; j < 8; ++j) f ^= lanes[j];
+        folds[(size_t)t] = f;
+    };
+    std::vector<std::thread> pool;
+    for (int t = 1; t < n; ++t) pool.emplace_back(worker, t);
+    worker(0);
+    for (auto& th : pool) th.join();
+    uint64_t f = 0;
+    for (uint64_t x : folds) f ^= x;
+    *sink = f;
+    return OMNI_OK;
+}
