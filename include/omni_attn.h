@@ -314,6 +314,17 @@ omni_status omni_queue_pop(const omni_queue* q, void* rows_out, int32_t* tags_ou
                            int32_t* n_popped, void* hip_stream);
 
 /*
+ * Row offsets for rows that came out of an output queue, so that they can be a CSR source of
+ * omni_merge_partials without a trip to the host: tags [max_rows] (device) hold the sequence number of each
+ * popped row, *n_rows (device int32, NULL = max_rows) how many there are; the tags must be non-decreasing
+ * (rows of a sequence together, sequences in batch order: the order a producer that works through the batch
+ * pushes them in).  Writes row_offsets [batch + 1] (device): row_offsets[i] = number of rows with a tag below
+ * i.  Rows with tags outside [0, batch) fall outside every sequence's range.  Errors: NULL, SHAPE, LAUNCH.
+ */
+omni_status omni_csr_from_tags(const int32_t* tags, const int32_t* n_rows, int32_t max_rows, int32_t batch,
+                               int32_t* row_offsets, void* hip_stream);
+
+/*
  * Residual store [n_slots, row_bytes]: save rows [n_rows, row_bytes] to slots slot_ids[r] (the caller
  * maps (request, layer) to a slot), or load those slots into rows.  Slot ids outside [0, n_slots) are
  * skipped on save and give zero rows on load.  Errors: NULL, SHAPE, LAUNCH.

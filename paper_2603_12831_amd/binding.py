@@ -27,7 +27,7 @@ EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_deco
            "omni_status_string", "omni_debug_gather_kv", "omni_debug_stream_read", "omni_debug_copy",
            "omni_debug_host_stream_read",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
-           "omni_queue_push", "omni_queue_pop", "omni_residual_save", "omni_residual_load",
+           "omni_queue_push", "omni_queue_pop", "omni_csr_from_tags", "omni_residual_save", "omni_residual_load",
            "omni_host_partial_attn", "omni_debug_sort_bin", "omni_debug_ticket_map")
 
 
@@ -135,6 +135,8 @@ def load_library() -> ctypes.CDLL:
         lib.omni_queue_push.restype = ctypes.c_int
         lib.omni_queue_pop.argtypes = [qp, vp, vp, ctypes.c_int32, vp, vp]
         lib.omni_queue_pop.restype = ctypes.c_int
+        lib.omni_csr_from_tags.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        lib.omni_csr_from_tags.restype = ctypes.c_int
         lib.omni_residual_save.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
         lib.omni_residual_save.restype = ctypes.c_int
         lib.omni_residual_load.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
@@ -457,6 +459,18 @@ def omni_queue_pop(q: omni_queue, rows_out, tags_out=None, n_popped=None, stream
                                        _dev_ptr(n_popped, "n_popped", torch.int32), _stream_ptr(stream))
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_queue_pop")
+    return st
+
+
+def omni_csr_from_tags(tags, n_rows, batch: int, row_offsets, stream=None, check: bool = True) -> int:
+    """tags int32 [max_rows], n_rows int32 [1] or None, row_offsets int32 [batch + 1] (all on the GPU)."""
+    if row_offsets.numel() != batch + 1:
+        raise ValueError("row_offsets must have batch + 1 entries")
+    st = load_library().omni_csr_from_tags(_dev_ptr(tags, "tags", torch.int32), _dev_ptr(n_rows, "n_rows", torch.int32),
+                                           tags.numel(), int(batch), _dev_ptr(row_offsets, "row_offsets", torch.int32),
+                                           _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_csr_from_tags")
     return st
 
 

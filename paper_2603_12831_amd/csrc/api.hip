@@ -307,6 +307,15 @@ omni_status omni_queue_pop(const omni_queue* q, void* rows_out, int32_t* tags_ou
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
 
+omni_status omni_csr_from_tags(const int32_t* tags, const int32_t* n_rows, int32_t max_rows, int32_t batch,
+                               int32_t* row_offsets, void* hip_stream)
+{
+    if (max_rows < 0 || batch < 0) return OMNI_ERR_SHAPE;
+    if (!row_offsets || (max_rows > 0 && !tags)) return OMNI_ERR_NULL;
+    hipError_t e = launch_csr_from_tags(tags, n_rows, max_rows, batch, row_offsets, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
+}
+
 static omni_status residual(void* store, int64_t n_slots, int32_t row_bytes, const int32_t* slot_ids, int32_t n_rows,
                             void* rows, bool save, void* hip_stream)
 {

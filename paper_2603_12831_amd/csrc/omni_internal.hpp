@@ -126,6 +126,7 @@ hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hip
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_queue(const QueueParams& q, bool push, const void* src_rows, const int* src_tags, void* dst_rows,
                         int* dst_tags, int n_rows, int* n_done, hipStream_t s);
+hipError_t launch_csr_from_tags(const int* tags, const int* n_rows, int max_rows, int batch, int* offsets, hipStream_t s);
 hipError_t launch_store(void* store, long long n_slots, int row_bytes, const int* slot_ids, int n_rows, void* rows,
                         bool save, hipStream_t s);
 hipError_t launch_kv_append(const KvParams& c, const void* k_new, const void* v_new, const int* positions, hipStream_t s);

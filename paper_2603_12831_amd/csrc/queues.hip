@@ -99,6 +99,26 @@ __global__ __launch_bounds__(256) void store_kernel(u32x4* store, long long n_sl
     }
 }
 
+// CSR offsets of popped rows: tags[0 .. n) (n read on the device, at most max_rows) are the sequence numbers
+// of the rows, non-decreasing (rows of one sequence together, sequences in order - the order in which a
+// producer that works through the batch pushes them); offsets[i] = number of rows with a tag below i, so
+// rows offsets[i] .. offsets[i+1]-1 are sequence i's.  One thread per offset, a binary search each.
+__global__ __launch_bounds__(256) void csr_from_tags_kernel(const int* __restrict__ tags, const int* __restrict__ n_rows,
+                                                            int max_rows, int batch, int* __restrict__ offsets)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > batch) return;
+    int n = n_rows ? *n_rows : max_rows;
+    n = n < 0 ? 0 : (n > max_rows ? max_rows : n);
+    int lo = 0, hi = n;                                    // first row whose tag is >= i
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (tags[mid] < i) lo = mid + 1;
+        else hi = mid;
+    }
+    offsets[i] = lo;
+}
+
 // few workgroups: every workgroup of a queue call ends with an atomic on one word, and those are served
 // one after the other; the moves per lane are unrolled instead
 unsigned grid_for(long long pieces)
@@ -119,6 +139,13 @@ hipError_t launch_queue(const QueueParams& q, bool push, const void* src_rows, c
     else
         hipLaunchKernelGGL((queue_kernel<false>), dim3(grid), dim3(256), 0, s, q, static_cast<const u32x4*>(src_rows),
                            src_tags, static_cast<u32x4*>(dst_rows), dst_tags, n_rows, n_done);
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_from_tags(const int* tags, const int* n_rows, int max_rows, int batch, int* offsets, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((batch + 1 + 255) / 256);
+    hipLaunchKernelGGL(csr_from_tags_kernel, dim3(grid), dim3(256), 0, s, tags, n_rows, max_rows, batch, offsets);
     return hipGetLastError();
 }
 

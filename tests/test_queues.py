@@ -117,3 +117,63 @@ def test_gpu_queue_and_store_match_the_oracle():
         binding.omni_residual_load(store_d, torch.from_numpy(probe).to(dev), out)
         assert np.array_equal(out.view(torch.uint8).cpu().numpy().reshape(400, -1), oracle.store_load(store_h, probe))
     assert np.array_equal(store_d.view(torch.uint8).cpu().numpy().reshape(n_slots, -1), store_h)
+
+
+@pytest.mark.gpu
+def test_gpu_rows_from_the_output_queue_feed_the_merge():
+    """The piggybacking data path end to end on a config-4-shaped batch: the host producer computes the
+    prefix partials of the best-effort rows (KV in host memory), they are pushed into device-resident output
+    queues (O rows and LSE rows, tagged with the sequence number) in three instalments, popped, given their
+    CSR offsets on the device from the tags and the popped count, and merged with the GPU's tail partials:
+    the result must be attention over the full contexts (oracle), and the popped rows the pushed ones."""
+    torch = pytest.importorskip("torch")
+    from paper_2603_12831_amd import binding, workloads as wl
+    from paper_2603_12831_amd.runner import DeviceWorkload
+    assert torch.cuda.is_available()
+    dev = torch.device("cuda:0")
+    w = wl.make_cfg4(n_ls=4, n_be=23, ls_lo=20, ls_hi=400, be_lo=300, be_hi=1500, tail_lo=5, tail_hi=90)
+    seq = np.array([i for i, rs in enumerate(w.ext_ranges) for _ in rs], dtype=np.int32)
+    begin = np.array([b for rs in w.ext_ranges for (b, _) in rs], dtype=np.int32)
+    end = np.array([e for rs in w.ext_ranges for (_, e) in rs], dtype=np.int32)
+    ext_o, ext_l = binding.omni_host_partial_attn(w.q, w.k_pool, w.v_pool, w.block_table, seq, begin, end,
+                                                  w.sm_scale, w.dtype, n_threads=8)
+    n, hq, d = len(seq), w.num_q_heads, w.head_dim
+    cap = n + 5
+    # (the queue struct holds addresses only: the tensors must stay alive beside it)
+    mem_o = (torch.zeros((cap, hq * d * 4), dtype=torch.uint8, device=dev), torch.zeros(cap, dtype=torch.int32, device=dev),
+             torch.zeros(4, dtype=torch.int32, device=dev))
+    mem_l = (torch.zeros((cap, hq * 4), dtype=torch.uint8, device=dev), torch.zeros(cap, dtype=torch.int32, device=dev),
+             torch.zeros(4, dtype=torch.int32, device=dev))
+    qo, ql = binding.make_queue(*mem_o), binding.make_queue(*mem_l)
+    o_dev = torch.from_numpy(ext_o).to(dev)
+    l_dev = torch.from_numpy(ext_l).to(dev)
+    tags = torch.from_numpy(seq).to(dev)
+    cuts = [0, n // 3, n // 3 + 1, n]
+    for a, b in zip(cuts[:-1], cuts[1:]):                            # the producer's rows arrive in instalments
+        binding.omni_queue_push(qo, o_dev[a:b].reshape(b - a, -1).view(torch.uint8), tags[a:b])
+        binding.omni_queue_push(ql, l_dev[a:b].reshape(b - a, -1).view(torch.uint8), tags[a:b])
+    # the consumer: pop whatever is there (room for more rows than came), offsets from the tags, merge
+    got_o = torch.full((cap, hq, d), float("nan"), dtype=torch.float32, device=dev)
+    got_l = torch.full((cap, hq), float("nan"), dtype=torch.float32, device=dev)
+    got_t = torch.full((cap,), -9, dtype=torch.int32, device=dev)
+    n_o = torch.zeros(1, dtype=torch.int32, device=dev)
+    n_l = torch.zeros(1, dtype=torch.int32, device=dev)
+    binding.omni_queue_pop(qo, got_o.view(torch.uint8).reshape(cap, -1), got_t, n_o)
+    binding.omni_queue_pop(ql, got_l.view(torch.uint8).reshape(cap, -1), None, n_l)
+    offsets = torch.full((w.batch + 1,), -1, dtype=torch.int32, device=dev)
+    binding.omni_csr_from_tags(got_t, n_o, w.batch, offsets)
+    # (built as a batch with an external source, which is then the popped rows as they lie on the device)
+    dw = DeviceWorkload(w, out_dtype="f32", ext_o=np.zeros((1, hq, d), dtype=np.float32),
+                        ext_lse=np.zeros((1, hq), dtype=np.float32), ext_offsets=np.zeros(w.batch + 1, dtype=np.int32))
+    dw.ext = (got_o, got_l, offsets, 0)
+    dw.poison_outputs()
+    dw.run()
+    res_o, res_l = dw.results()
+    assert int(n_o.item()) == n and int(n_l.item()) == n
+    assert np.array_equal(offsets.cpu().numpy(), wl.ext_row_offsets(w))
+    assert np.array_equal(offsets.cpu().numpy(), np.searchsorted(seq, np.arange(w.batch + 1)))
+    assert torch.equal(got_o[:n], o_dev) and torch.equal(got_l[:n], l_dev)
+    full_end = np.max(np.stack([c.ctx_end for c in w.calls]), axis=0)
+    exp_o, exp_l = oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, np.zeros_like(full_end), full_end,
+                                     w.sm_scale, w.dtype, n_threads=8)
+    assert float(np.max(np.abs(res_o - exp_o))) <= 2e-3 and float(np.max(np.abs(res_l - exp_l))) <= 2e-3
