@@ -123,16 +123,26 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
 }
 
-// One 4 KiB tile (K or V of one page and kv head) into four 16-byte registers per lane; `stride` is
-// the byte distance between the lane's four loads.  An absent page (< 0) reads page 0 instead, so the
-// load is always in bounds; the caller masks every token of such a page.
-__device__ __forceinline__ void load_tile(const void* __restrict__ pool, int hkv, long long page, int kvh,
-                                          int lane_off, int stride, u32x4 (&r)[4])
+// A step's pages travel as 64-bit words: the physical page in the low 48 bits and, above bit 56, how many
+// of its 16 tokens the item attends from the start of the page (the item's last page may end early); a
+// negative word is an absent page.  Loads of a page go through a buffer resource that ends with the last
+// attended token, so the rows behind it (and all of an absent page) are neither fetched nor written: they
+// read as zero, and the caller masks those tokens anyway.
+constexpr int kPageTokenShift = 56;
+__device__ __forceinline__ long long page_word(long long page, int tokens) { return page | ((long long)tokens << kPageTokenShift); }
+__device__ __forceinline__ long long page_of(long long word) { return word < 0 ? 0 : (word & ((1ll << 48) - 1)); }
+__device__ __forceinline__ int page_bytes(long long word) { return word < 0 ? 0 : (int)(word >> kPageTokenShift) * (kD * 2); }
+
+// One 4 KiB tile (V of one page and kv head) into four 16-byte registers per lane: lane l reads bytes
+// lane_off .. +15 of each KiB (non-temporal).
+__device__ __forceinline__ void load_tile(const void* __restrict__ pool, int hkv, long long word, int kvh,
+                                          int lane_off, u32x4 (&r)[4])
 {
-    const long long pg = page < 0 ? 0 : page;
-    const char* src = static_cast<const char*>(pool) + (pg * hkv + kvh) * (long long)kPageBytes + lane_off;
+    constexpr int kNonTemporal = 2;
+    const char* src = static_cast<const char*>(pool) + (page_of(word) * hkv + kvh) * (long long)kPageBytes;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(src), 0, page_bytes(word), 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i * stride));
+    for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off + i * 1024, 0, kNonTemporal);
 }
 
 // physical pages of step s of an item (s wave-uniform); pages past the item's last page, or whose
@@ -143,11 +153,11 @@ __device__ __forceinline__ Pages step_pages(const DecodeParams& p, const Item& i
     const int lp = __builtin_amdgcn_readfirstlane(it.lp_first + 2 * s);
     if (lp <= it.lp_last) {
         long long pg = load_invariant(it.table + lp);
-        r.a = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
+        r.a = (pg >= 0 && pg < p.num_blocks) ? page_word(pg, min(kBlockSize, it.ce - (lp << 4))) : -1;
     }
     if (lp + 1 <= it.lp_last) {
         long long pg = load_invariant(it.table + lp + 1);
-        r.b = (pg >= 0 && pg < p.num_blocks) ? pg : -1;
+        r.b = (pg >= 0 && pg < p.num_blocks) ? page_word(pg, min(kBlockSize, it.ce - ((lp + 1) << 4))) : -1;
     }
     return r;
 }
@@ -164,7 +174,7 @@ constexpr int kAuxK = 2;                               // cache policy of the K 
 // flight).  A wave-wide 16-byte direct load puts lane s's data at base + 16 s, so for KiB i of a page
 // lane s fetches token 4i + s/16, 16-byte chunk (s%16) ^ token: the global side stays whole 256-byte
 // rows per 16 lanes, and the LDS image is XOR-swizzled so that the later operand reads (16 lanes =
-// 16 different tokens, same chunk) touch every bank once.  An absent page reads page 0 (masked later).
+// 16 different tokens, same chunk) touch every bank once.
 // Buffer-addressed direct loads are used (not flat/global ones): the compiler then keeps exact counts of
 // the vector-memory operations in flight instead of draining them all at the next register-load wait.
 __device__ __forceinline__ void issue_k(const DecodeParams& p, int kvh, Pages pg, int lane, char* stage)
@@ -173,10 +183,9 @@ __device__ __forceinline__ void issue_k(const DecodeParams& p, int kvh, Pages pg
     const int v0 = row * (kD * 2) + ((chunk ^ row) & 15) * 16;          // byte offset in KiB 0; KiB i: ^ (i << 6)
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-        const long long page = half ? pg.b : pg.a;
-        const long long pgc = page < 0 ? 0 : page;
-        const char* src = static_cast<const char*>(p.k_pool) + (pgc * p.hkv + kvh) * (long long)kPageBytes;
-        const __amdgpu_buffer_rsrc_t rs = byte_buffer(src, kPageBytes);
+        const long long word = half ? pg.b : pg.a;
+        const char* src = static_cast<const char*>(p.k_pool) + (page_of(word) * p.hkv + kvh) * (long long)kPageBytes;
+        const __amdgpu_buffer_rsrc_t rs = byte_buffer(src, page_bytes(word));
         char* dst = stage + half * kPageBytes;
         // the instruction's immediate offset moves both the memory address and the LDS address
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)dst, 16, v0, 0, 0, kAuxK);
@@ -196,8 +205,8 @@ __device__ __forceinline__ u32x4 read_k(const char* stage, int half, int kb, int
 
 __device__ __forceinline__ void issue_v(const DecodeParams& p, int kvh, Pages pg, int v_lane_off, StepRegs& r)
 {
-    load_tile(p.v_pool, p.hkv, pg.a, kvh, v_lane_off, 1024, r.va);      // token 4i + kg, dims col*8 ..
-    load_tile(p.v_pool, p.hkv, pg.b, kvh, v_lane_off, 1024, r.vb);
+    load_tile(p.v_pool, p.hkv, pg.a, kvh, v_lane_off, r.va);            // token 4i + kg, dims col*8 ..
+    load_tile(p.v_pool, p.hkv, pg.b, kvh, v_lane_off, r.vb);
 }
 
 // Request a whole step: the 8 K loads strictly before the 8 V loads (the in-order counting of
@@ -416,10 +425,10 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
     if (s < it.n_steps) {
         const Tail tail = before_last();
         // `chained`: the step always ends with a request (the next item's first step, or, when there is
-        // none, a throw-away re-read of page 0), so that one copy of the step code with exact load
+        // none, the same loads on two absent pages, which fetch nothing), so that one copy of the step code with exact load
         // counts serves; a second copy for "nothing follows" cost registers to the point of spilling
         if (chained) attend_step<true>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0,
-                                       tail.valid ? tail.pages : Pages{0, 0}, tail.valid ? tail.kvh : 0, scale2);
+                                       tail.valid ? tail.pages : Pages{-1, -1}, tail.valid ? tail.kvh : 0, scale2);
         else attend_step<false>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.pages, tail.kvh, scale2);
         after_last();
     }
