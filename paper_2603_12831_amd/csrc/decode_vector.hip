@@ -1,12 +1,18 @@
-// Vector-ALU decode attention: the any-shape kernel (fp32 or bf16, head_dim 64
-// or 128, any GQA ratio).  One workgroup of four waves per (sequence, chunk,
-// query head).  A wave looks at four tokens at a time: sixteen lanes share a
-// token row, each lane holding head_dim/16 consecutive dims, so a wave load
-// covers whole contiguous rows.  Each 16-lane group keeps its own online-
-// softmax state over the tokens it sees; the sixteen states of the workgroup
-// are combined through LDS at the end with the same log-sum-exp rule the
-// merge uses.  Computes Eq. 1 of the paper's Background section restricted to
-// the chunk.
+// Vector-ALU decode attention: the any-shape kernel (fp32 or bf16, head_dim 64 or 128, any GQA ratio up to
+// 16).  One workgroup of four waves per (sequence, chunk, kv head): every KV byte of the chunk is read once
+// and serves all G query heads that share the kv head (Eq. 1 of the paper's Background section for G
+// queries at a time, restricted to the chunk); with more than eight heads to a kv head, two workgroups
+// take eight heads each (the register file holds the states of eight).
+//
+// A wave looks at four tokens at a time: sixteen lanes share a token row, each lane holding head_dim/16
+// consecutive dims, so a wave load covers whole contiguous rows.  A lane takes kUnroll tokens per turn
+// (their loads go out together), forms the G dot products of each (partial sums over its dims, then a
+// sum over the sixteen lanes of the row), and updates the online-softmax state of its 16-lane group
+// once per turn: one running maximum, sum and accumulator slice per head.  The sixteen group states of the
+// workgroup are combined at the end with the same log-sum-exp rule the merge uses: the four groups of a wave
+// by lane shuffles, the four waves through LDS.
+#include <type_traits>
+
 #include "omni_internal.hpp"
 
 namespace omni {
@@ -42,107 +48,209 @@ template <> struct RowVec<uint16_t, 8> {
     }
 };
 
+// Sum over the sixteen lanes that share a token row, left in every one of them: four adds whose second
+// operand comes through the data-parallel lane permutes (neighbour in the pair, other pair of the quad,
+// mirrored half row, mirrored row) - vector-ALU instructions, where lane shuffles would go through the LDS
+// pipe, which four waves of a CU share (the shuffles were what bounded this kernel).
+__device__ __forceinline__ float row16_sum(float x)
+{
+    constexpr int kQuadPerm1032 = 0xB1, kQuadPerm2301 = 0x4E, kRowHalfMirror = 0x141, kRowMirror = 0x140;
+    auto from = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                     0xf, 0xf, true));
+    };
+    x += from(x, std::integral_constant<int, kQuadPerm1032>{});
+    x += from(x, std::integral_constant<int, kQuadPerm2301>{});
+    x += from(x, std::integral_constant<int, kRowHalfMirror>{});
+    x += from(x, std::integral_constant<int, kRowMirror>{});
+    return x;
+}
+
 constexpr int kWaves = 4;
 constexpr int kGroups = kWaves * 4;            // 16-lane groups per workgroup
+constexpr int kUnroll = 4;                     // tokens a 16-lane group takes per turn
 
-template <typename T, int D>
+// GMAX: compile-time bound of the heads per kv head the instance serves (registers are sized for it)
+template <typename T, int D, int GMAX>
 __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodeParams p)
 {
     constexpr int E = D / 16;
-    const int head = blockIdx.x, chunk = blockIdx.y, seq = blockIdx.z;
+    const int splits = (p.group + GMAX - 1) / GMAX;             // workgroups that share a kv head's heads
+    const int kvh = blockIdx.x / splits, chunk = blockIdx.y, seq = blockIdx.z;
+    const int head0 = kvh * p.group + (blockIdx.x % splits) * GMAX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15;                 // which E dims of the row
-    const int grp = wave * 4 + (lane >> 4);    // which token of each 16-token step
-    const int kvh = head / p.group;
+    const int grp = wave * 4 + (lane >> 4);    // which token of each 16-token turn
+    const int G = min(GMAX, (kvh + 1) * p.group - head0);       // heads of this workgroup: head0 .. head0 + G - 1
 
     int b, e, cb, ce;
     seq_range(p, seq, b, e);
     chunk_range(p, b, e, chunk, cb, ce);
     // a sequence with at most one non-empty chunk (chunk 0) gets its final row from this kernel
     const bool seq_direct = p.out_o != nullptr && live_chunks(p, b, e) <= 1;
-    if (p.seq_final && head == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
+    if (p.seq_final && blockIdx.x == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
 
-    float q[E];
-    RowVec<T, E>::load(p.q, ((long long)seq * p.hq + head) * D + sub * E, q);
-
-    float m = -INFINITY, l = 0.f, acc[E];
+    // bf16 inputs (tolerance 2e-3): logits in the log2 domain and the hardware's exp2 / log2; fp32 inputs
+    // (tolerance 1e-5): natural units and the library's expf / logf
+    constexpr bool kLog2 = !std::is_same<T, float>::value;
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    const float qscale = kLog2 ? p.sm_scale * kLog2e : p.sm_scale;
+    auto ex = [](float x) { return kLog2 ? __builtin_amdgcn_exp2f(x) : expf(x); };
+    float q[GMAX][E];
 #pragma unroll
-    for (int i = 0; i < E; ++i) acc[i] = 0.f;
+    for (int g = 0; g < GMAX; ++g) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) q[g][i] = 0.f;
+        if (g < G) {
+            RowVec<T, E>::load(p.q, ((long long)seq * p.hq + head0 + g) * D + sub * E, q[g]);
+#pragma unroll
+            for (int i = 0; i < E; ++i) q[g][i] *= qscale;
+        }
+    }
+    float m[GMAX], l[GMAX], acc[GMAX][E];
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[g][i] = 0.f;
+    }
 
     const int* table = p.block_table + (long long)seq * p.max_blocks;
-    for (int t = cb + grp; t < ce; t += kGroups) {
-        long long page = table[t >> 4];
-        if (page < 0 || page >= p.num_blocks) continue;      // absent page: its tokens do not exist
-        long long row = ((page * p.hkv + kvh) * kBlockSize + (t & 15)) * D + sub * E;
-        float kx[E], vx[E];
-        RowVec<T, E>::load(p.k_pool, row, kx);
-        RowVec<T, E>::load(p.v_pool, row, vx);
-        float dot = 0.f;
+    for (int t0 = cb + grp; t0 < ce; t0 += kGroups * kUnroll) {
+        float kx[kUnroll][E], vx[kUnroll][E];
+        bool live[kUnroll];
 #pragma unroll
-        for (int i = 0; i < E; ++i) dot = fmaf(q[i], kx[i], dot);
-        dot += __shfl_xor(dot, 1);
-        dot += __shfl_xor(dot, 2);
-        dot += __shfl_xor(dot, 4);
-        dot += __shfl_xor(dot, 8);
-        float s = dot * p.sm_scale;
-        float m_new = fmaxf(m, s);
-        float corr = expf(m - m_new);                        // exp(-inf) = 0 on the first token
-        float w = expf(s - m_new);
-        l = l * corr + w;
+        for (int u = 0; u < kUnroll; ++u) {
+            const int t = t0 + u * kGroups;
+            long long page = t < ce ? table[t >> 4] : -1;
+            live[u] = page >= 0 && page < p.num_blocks;          // absent page: its tokens do not exist
+            const long long row = live[u] ? ((page * p.hkv + kvh) * kBlockSize + (t & 15)) * D + sub * E : 0;
+            RowVec<T, E>::load(p.k_pool, row, kx[u]);
+            RowVec<T, E>::load(p.v_pool, row, vx[u]);
+        }
+        // a token that is not there: its weight will be zero, and its V must not reach the sums (0 * NaN)
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] = acc[i] * corr + w * vx[i];
-        m = m_new;
+        for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+            for (int i = 0; i < E; ++i) vx[u][i] = live[u] ? vx[u][i] : 0.f;
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) {
+            if (g >= G) break;
+            float s[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float dot = 0.f;
+#pragma unroll
+                for (int i = 0; i < E; ++i) dot = fmaf(q[g][i], kx[u][i], dot);
+                s[u] = live[u] ? row16_sum(dot) : -INFINITY;
+            }
+            float m_new = m[g];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) m_new = fmaxf(m_new, s[u]);
+            if (m_new == -INFINITY) continue;                    // nothing live in this turn, nothing before
+            const float corr = ex(m[g] - m_new);                 // exp(-inf) = 0 on the first live token
+            float w[kUnroll], wsum = 0.f;
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                w[u] = ex(s[u] - m_new);                         // exp(-inf) = 0 for a token that is not there
+                wsum += w[u];
+            }
+            l[g] = l[g] * corr + wsum;
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+                float a = acc[g][i] * corr;
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) a = fmaf(w[u], vx[u][i], a);
+                acc[g][i] = a;
+            }
+            m[g] = m_new;
+        }
     }
 
-    __shared__ float sh_m[kGroups], sh_l[kGroups], sh_acc[kGroups][D];
-    if (sub == 0) { sh_m[grp] = m; sh_l[grp] = l; }
+    // the four groups of a wave first (lanes 16 and 32 apart hold the same dims of the same head) ...
 #pragma unroll
-    for (int i = 0; i < E; ++i) sh_acc[grp][sub * E + i] = acc[i];
+    for (int g = 0; g < GMAX; ++g) {
+        if (g >= G) break;
+#pragma unroll
+        for (int d = 16; d <= 32; d <<= 1) {
+            const float m_o = __shfl_xor(m[g], d), l_o = __shfl_xor(l[g], d);
+            const float m_new = fmaxf(m[g], m_o);
+            const float f_me = m[g] == -INFINITY ? 0.f : ex(m[g] - m_new);
+            const float f_o = m_o == -INFINITY ? 0.f : ex(m_o - m_new);
+            l[g] = l[g] * f_me + l_o * f_o;
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[g][i] = acc[g][i] * f_me + __shfl_xor(acc[g][i], d) * f_o;
+            m[g] = m_new;
+        }
+    }
+    // ... then the four waves through LDS
+    extern __shared__ float sh[];                                // [kWaves][G] m, [kWaves][G] l, [kWaves][G][D] acc
+    float* sh_m = sh;
+    float* sh_l = sh + kWaves * G;
+    float* sh_acc = sh + 2 * kWaves * G;
+    if (lane < 16) {
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) {
+            if (g >= G) break;
+            if (sub == 0) { sh_m[wave * G + g] = m[g]; sh_l[wave * G + g] = l[g]; }
+#pragma unroll
+            for (int i = 0; i < E; ++i) sh_acc[(wave * G + g) * D + sub * E + i] = acc[g][i];
+        }
+    }
     __syncthreads();
 
-    const int dim = threadIdx.x;
-    if (dim >= D) return;
-    float mm = -INFINITY;
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) mm = fmaxf(mm, sh_m[g]);
-    const long long prow = ((long long)seq * p.max_chunks + chunk) * p.hq + head;
     const bool final_row = seq_direct && chunk == 0;
     const bool partial_row = !seq_direct || p.max_chunks == 1;     // a one-slot call keeps the partial as well
-    const long long orow = (long long)seq * p.hq + head;
-    float o = 0.f, lse = -INFINITY;
-    if (mm != -INFINITY) {
-        float ll = 0.f, oo = 0.f;
+    for (int idx = threadIdx.x; idx < G * D; idx += kWaves * kWave) {
+        const int g = idx / D, dim = idx - g * D;
+        float mm = -INFINITY;
 #pragma unroll
-        for (int g = 0; g < kGroups; ++g) {
-            float w = (sh_m[g] == -INFINITY) ? 0.f : expf(sh_m[g] - mm);
-            ll += w * sh_l[g];
-            oo += w * sh_acc[g][dim];
+        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, sh_m[w * G + g]);
+        const long long prow = ((long long)seq * p.max_chunks + chunk) * p.hq + head0 + g;
+        const long long orow = (long long)seq * p.hq + head0 + g;
+        float o = 0.f, lse = -INFINITY;
+        if (mm != -INFINITY) {
+            float ll = 0.f, oo = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float mw = sh_m[w * G + g];
+                const float f = (mw == -INFINITY) ? 0.f : ex(mw - mm);
+                ll += f * sh_l[w * G + g];
+                oo += f * sh_acc[(w * G + g) * D + dim];
+            }
+            o = oo / ll;
+            lse = kLog2 ? (mm + __builtin_amdgcn_logf(ll)) * kLn2 : mm + logf(ll);      // (v_log_f32 is log2)
+            if (p.part_o && partial_row) p.part_o[prow * D + dim] = o;
         }
-        o = oo / ll;
-        lse = mm + logf(ll);
-        if (p.part_o && partial_row) p.part_o[prow * D + dim] = o;
+        if (p.part_lse && dim == 0) p.part_lse[prow] = partial_row ? lse : -INFINITY;
+        if (final_row) {
+            if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow * D + dim] = f32_to_bf16(o);
+            else static_cast<float*>(p.out_o)[orow * D + dim] = o;
+            if (p.out_lse && dim == 0) p.out_lse[orow] = lse;
+        }
     }
-    if (p.part_lse && dim == 0) p.part_lse[prow] = partial_row ? lse : -INFINITY;
-    if (final_row) {
-        if (p.out_bf16) static_cast<uint16_t*>(p.out_o)[orow * D + dim] = f32_to_bf16(o);
-        else static_cast<float*>(p.out_o)[orow * D + dim] = o;
-        if (p.out_lse && dim == 0) p.out_lse[orow] = lse;
-    }
+}
+
+template <typename T, int D>
+hipError_t launch_for_group(const DecodeParams& p, hipStream_t s)
+{
+    const int per = p.group <= 1 ? 1 : (p.group <= 4 ? 4 : 8);            // heads a workgroup serves at most
+    const int splits = (p.group + per - 1) / per;
+    dim3 grid(p.hkv * splits, p.max_chunks, p.batch), block(kWaves * kWave);
+    const size_t lds = (size_t)(2 * kWaves * per + kWaves * per * D) * sizeof(float);
+    if (per == 1) hipLaunchKernelGGL((decode_vector_kernel<T, D, 1>), grid, block, lds, s, p);
+    else if (per == 4) hipLaunchKernelGGL((decode_vector_kernel<T, D, 4>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((decode_vector_kernel<T, D, 8>), grid, block, lds, s, p);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s)
 {
-    dim3 grid(p.hq, p.max_chunks, p.batch), block(kWaves * kWave);
-    if (bf16) {
-        if (p.d == 64) hipLaunchKernelGGL((decode_vector_kernel<uint16_t, 64>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((decode_vector_kernel<uint16_t, 128>), grid, block, 0, s, p);
-    } else {
-        if (p.d == 64) hipLaunchKernelGGL((decode_vector_kernel<float, 64>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((decode_vector_kernel<float, 128>), grid, block, 0, s, p);
-    }
-    return hipGetLastError();
+    if (bf16) return p.d == 64 ? launch_for_group<uint16_t, 64>(p, s) : launch_for_group<uint16_t, 128>(p, s);
+    return p.d == 64 ? launch_for_group<float, 64>(p, s) : launch_for_group<float, 128>(p, s);
 }
 
 }  // namespace omni
