@@ -93,7 +93,8 @@ omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_b
         if (ws_bytes < decode_workspace_bytes(p.batch, p.max_chunks, p.hkv)) return OMNI_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return OMNI_ERR_SHAPE;
     }
-    if (p.fuse && !ws) return OMNI_ERR_UNSUPPORTED;        // only the persistent form finishes every sequence
+    // only the persistent form finishes every sequence, and only at head_dim 128
+    if (p.fuse && (!ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
     hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
@@ -159,6 +160,7 @@ const char* omni_decode_kernel_name(const omni_decode_args* a)
     if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return "";
     if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
     if (!mfma) return (p.fuse || a->kernel > OMNI_KERNEL_MFMA || a->kernel < 0) ? "" : "decode_vector_kernel";
+    if (p.fuse && p.d != 128) return "";
     if (!a->workspace) return p.fuse ? "" : "decode_mfma_grid_kernel";
     return "decode_mfma_persistent_kernel";
 }

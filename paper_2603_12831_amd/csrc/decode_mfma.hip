@@ -37,6 +37,15 @@
 // accumulator only when some maximum of the wave moved.  The four waves'
 // states are combined through LDS with the log-sum-exp rule.
 //
+// head_dim 64 rides on the same tiles ("half" instances): the 2 KiB tiles of two neighbouring kv heads of a
+// page are one contiguous 4 KiB run, which read as sixteen 256-byte rows holds in row r the tokens 2 (r % 8)
+// and 2 (r % 8) + 1 of kv head r / 8, side by side.  A query head of either kv head then becomes two columns
+// of the Q^T operand, its 64 dims in the even-token or in the odd-token half of the 128 and zeros in the
+// other, so that S^T[r, column] is the logit of one token of one head (entries whose row belongs to the
+// other kv head are masked), the weights enter P^T exactly as before, and O^T comes out with the even
+// tokens' sum in dims 0..63 of one column and the odd tokens' in dims 64..127 of its neighbour, added up at
+// the end.  Four columns per query head pair up to G = 4; the streaming of K and V is untouched.
+//
 // Two launch forms share the per-step code:
 //   * grid form: one workgroup per (sequence, chunk, kv head) slot of the
 //     partial buffers, empty slots exit at once; needs no workspace.
@@ -124,14 +133,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
 }
 
 // A step's pages travel as 64-bit words: the physical page in the low 48 bits and, above bit 56, how many
-// of its 16 tokens the item attends from the start of the page (the item's last page may end early); a
+// 128-byte units from the start of its tile the item needs (the item's last page may end early); a
 // negative word is an absent page.  Loads of a page go through a buffer resource that ends with the last
 // attended token, so the rows behind it (and all of an absent page) are neither fetched nor written: they
-// read as zero, and the caller masks those tokens anyway.
+// read as zero, and the caller masks those tokens anyway.  A tile of 128-wide rows needs two units per
+// token; a pair of 64-wide tiles (`half`) needs all of the first tile and one unit per token of the second.
 constexpr int kPageTokenShift = 56;
-__device__ __forceinline__ long long page_word(long long page, int tokens) { return page | ((long long)tokens << kPageTokenShift); }
+template <bool half>
+__device__ __forceinline__ long long page_word(long long page, int tokens)
+{
+    return page | ((long long)(half ? kBlockSize + tokens : 2 * tokens) << kPageTokenShift);
+}
 __device__ __forceinline__ long long page_of(long long word) { return word < 0 ? 0 : (word & ((1ll << 48) - 1)); }
-__device__ __forceinline__ int page_bytes(long long word) { return word < 0 ? 0 : (int)(word >> kPageTokenShift) * (kD * 2); }
+__device__ __forceinline__ int page_bytes(long long word) { return word < 0 ? 0 : (int)(word >> kPageTokenShift) * kD; }
 
 // One 4 KiB tile (V of one page and kv head) into four 16-byte registers per lane: lane l reads bytes
 // lane_off .. +15 of each KiB (non-temporal).
@@ -147,17 +161,18 @@ __device__ __forceinline__ void load_tile(const void* __restrict__ pool, int hkv
 
 // physical pages of step s of an item (s wave-uniform); pages past the item's last page, or whose
 // table entry does not name a pool page, come back as -1
+template <bool half>
 __device__ __forceinline__ Pages step_pages(const DecodeParams& p, const Item& it, int s)
 {
     Pages r = {-1, -1};
     const int lp = __builtin_amdgcn_readfirstlane(it.lp_first + 2 * s);
     if (lp <= it.lp_last) {
         long long pg = load_invariant(it.table + lp);
-        r.a = (pg >= 0 && pg < p.num_blocks) ? page_word(pg, min(kBlockSize, it.ce - (lp << 4))) : -1;
+        r.a = (pg >= 0 && pg < p.num_blocks) ? page_word<half>(pg, min(kBlockSize, it.ce - (lp << 4))) : -1;
     }
     if (lp + 1 <= it.lp_last) {
         long long pg = load_invariant(it.table + lp + 1);
-        r.b = (pg >= 0 && pg < p.num_blocks) ? page_word(pg, min(kBlockSize, it.ce - ((lp + 1) << 4))) : -1;
+        r.b = (pg >= 0 && pg < p.num_blocks) ? page_word<half>(pg, min(kBlockSize, it.ce - ((lp + 1) << 4))) : -1;
     }
     return r;
 }
@@ -221,14 +236,24 @@ __device__ __forceinline__ void issue_step(const DecodeParams& p, int kvh, Pages
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// Q^T operands: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are zero columns
+// Q^T operands: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are zero columns.
+// `half`: column c stands for query row c / 2 of the kv-head pair (2 G rows of 64 dims) and token parity
+// c % 2: its 64 dims sit in that parity's half of the 128, the other half is zero.
+template <bool half>
 __device__ __forceinline__ void load_q(const DecodeParams& p, const Item& it, int col, int kg, u32x4 (&qb)[4])
 {
     const u32x4 z = {0, 0, 0, 0};
-    const long long row = (long long)it.seq * p.hq + (long long)it.kvh * p.group + col;
-    const char* qp = static_cast<const char*>(p.q) + (row * kD + kg * 8) * 2;
+    const long long row0 = (long long)it.seq * p.hq + (long long)it.kvh * p.group;       // in 256-byte rows
+    const char* q0 = static_cast<const char*>(p.q) + row0 * (kD * 2);
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) qb[kb] = (col < p.group) ? *reinterpret_cast<const u32x4*>(qp + kb * 64) : z;
+    for (int kb = 0; kb < 4; ++kb) {
+        if (half) {
+            const bool on = col < 4 * p.group && (kb >> 1) == (col & 1);
+            qb[kb] = on ? *reinterpret_cast<const u32x4*>(q0 + (col >> 1) * kD + ((kb & 1) * 4 + kg) * 16) : z;
+        } else {
+            qb[kb] = (col < p.group) ? *reinterpret_cast<const u32x4*>(q0 + col * (kD * 2) + (kb * 4 + kg) * 16) : z;
+        }
+    }
 }
 
 __device__ __forceinline__ void finish_item(Item& it, const int* __restrict__ block_table, int max_blocks)
@@ -290,7 +315,7 @@ struct LaneIds {
 // Vector-memory operations retire in order, and every request for a step is "8 K loads, then 8 V
 // loads": once at most 8 operations are outstanding the K tiles have landed, whatever was issued
 // after them.
-template <bool more>
+template <bool more, bool half>
 __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                             const u32x4 (&qb)[4], const LaneIds& id, int s, bool ok_a, bool ok_b,
                                             Pages next, int next_kvh, float scale2)
@@ -318,30 +343,52 @@ __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& i
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- logits to the log2 domain, masking on boundary steps -----------------------------------
-    const int t0 = (it.lp_first + 2 * s) << 4;             // first token of page A; register i is token 4i + kg
+    const int t0 = (it.lp_first + 2 * s) << 4;             // first token of page A; register i is tile row 4i + kg
     const bool interior = ok_a && ok_b && t0 >= it.cb && t0 + 32 <= it.ce;
     uint32_t vmask[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
 #pragma unroll
     for (int i = 0; i < 4; ++i) { sa[i] *= scale2; sb[i] *= scale2; }
-    if (!interior) {
+    if (!half) {
+        if (!interior) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ta = t0 + 4 * i + kg, tb = ta + 16;  // (tile row = token of the page)
+                const bool va = ok_a && ta >= it.cb && ta < it.ce;
+                const bool vb = ok_b && tb >= it.cb && tb < it.ce;
+                sa[i] = va ? sa[i] : -INFINITY;
+                sb[i] = vb ? sb[i] : -INFINITY;
+                // a masked token's V must not reach the MFMA (0 * NaN): V^T k-slot i (page A) or 4+i (page B);
+                // slots 2w, 2w+1 are the two halves of operand word w
+                const uint32_t keep = (i & 1) ? 0x0000ffffu : 0xffff0000u;
+                if (!va) vmask[i >> 1] &= keep;
+                if (!vb) vmask[2 + (i >> 1)] &= keep;
+            }
+        }
+    } else {
+        // tile row 4i + kg holds, of kv head i / 2 of the pair, the tokens 2 (4 (i % 2) + kg) + parity; a
+        // logit is real where the row's kv head is the column's and the column's token parity is attended
+        const int par = id.col & 1, kvsel = id.col >= 2 * p.group ? 1 : 0, par_v = id.col >> 3;
+        const bool col_on = id.col < 4 * p.group;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ta = t0 + 4 * i + kg, tb = ta + 16;
-            const bool va = ok_a && ta >= it.cb && ta < it.ce;
-            const bool vb = ok_b && tb >= it.cb && tb < it.ce;
-            sa[i] = va ? sa[i] : -INFINITY;
-            sb[i] = vb ? sb[i] : -INFINITY;
-            // a masked token's V must not reach the MFMA (0 * NaN): V^T k-slot i (page A) or 4+i (page B);
-            // slots 2w, 2w+1 are the two halves of operand word w
-            const uint32_t keep = (i & 1) ? 0x0000ffffu : 0xffff0000u;
-            if (!va) vmask[i >> 1] &= keep;
-            if (!vb) vmask[2 + (i >> 1)] &= keep;
+            const int ta = t0 + 2 * (4 * (i & 1) + kg) + par, tb = ta + 16;
+            const bool mine = col_on && (i >> 1) == kvsel;
+            sa[i] = (mine && ok_a && ta >= it.cb && ta < it.ce) ? sa[i] : -INFINITY;
+            sb[i] = (mine && ok_b && tb >= it.cb && tb < it.ce) ? sb[i] : -INFINITY;
+            if (!interior) {
+                // this lane's V^T rows are dims of the even-token (lanes 0..7 of 16) or odd-token half
+                const int tva = t0 + 2 * (4 * (i & 1) + kg) + par_v, tvb = tva + 16;
+                const uint32_t keep = (i & 1) ? 0x0000ffffu : 0xffff0000u;
+                if (!(ok_a && tva >= it.cb && tva < it.ce)) vmask[i >> 1] &= keep;
+                if (!(ok_b && tvb >= it.cb && tvb < it.ce)) vmask[2 + (i >> 1)] &= keep;
+            }
         }
     }
     // ---- online softmax ----------------------------------------------------------------------------
     float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (half) mx = fmaxf(mx, __shfl_xor(mx, 1));           // the two token parities of a head share its maximum
     const float m_new = fmaxf(st.m_run, mx);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // nothing seen yet: avoid inf - inf
     if (__any(m_new > st.m_run)) {
@@ -403,7 +450,7 @@ struct Tail {
 // after the wave's second-to-last step (if it has two or more).  The wave's last step is peeled off:
 // `before_last` runs right before it and returns what the wave requests during it instead of a further
 // step of this item, `after_last` runs right after it.
-template <bool chained, class Penult, class Before, class After>
+template <bool chained, bool half, class Penult, class Before, class After>
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                          const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur, Pages nxt,
                                          Penult&& at_penult, Before&& before_last, After&& after_last)
@@ -414,9 +461,9 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
     while (s + it.ds < it.n_steps) {
         const bool penult = s + 2 * it.ds >= it.n_steps;
         Pages nn = {-1, -1};
-        if (!penult) nn = step_pages(p, it, s + 2 * it.ds);                        // table reads run a step ahead
+        if (!penult) nn = step_pages<half>(p, it, s + 2 * it.ds);                        // table reads run a step ahead
         else at_penult(true);
-        attend_step<true>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2);
+        attend_step<true, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2);
         if (penult) at_penult(false);
         cur = nxt;
         nxt = nn;
@@ -427,9 +474,9 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
         // `chained`: the step always ends with a request (the next item's first step, or, when there is
         // none, the same loads on two absent pages, which fetch nothing), so that one copy of the step code with exact load
         // counts serves; a second copy for "nothing follows" cost registers to the point of spilling
-        if (chained) attend_step<true>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0,
+        if (chained) attend_step<true, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0,
                                        tail.valid ? tail.pages : Pages{-1, -1}, tail.valid ? tail.kvh : 0, scale2);
-        else attend_step<false>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.pages, tail.kvh, scale2);
+        else attend_step<false, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.pages, tail.kvh, scale2);
         after_last();
     }
 }
@@ -474,13 +521,20 @@ __device__ __forceinline__ void issue_q(const DecodeParams& p, const Item& it, i
 }
 
 // Q^T operands from the LDS copy: lane supplies head `col`, dims kb*32 + kg*8 .. +7; heads beyond G are
-// zero columns
+// zero columns (`half`: as in load_q)
+template <bool half>
 __device__ __forceinline__ void read_q(const char* qbuf, int group, int col, int kg, u32x4 (&qb)[4])
 {
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-        qb[kb] = (col < group) ? *reinterpret_cast<const u32x4*>(qbuf + col * (kD * 2) + (kb * 4 + kg) * 16) : z;
+    for (int kb = 0; kb < 4; ++kb) {
+        if (half) {
+            const bool on = col < 4 * group && (kb >> 1) == (col & 1);
+            qb[kb] = on ? *reinterpret_cast<const u32x4*>(qbuf + (col >> 1) * kD + ((kb & 1) * 4 + kg) * 16) : z;
+        } else {
+            qb[kb] = (col < group) ? *reinterpret_cast<const u32x4*>(qbuf + col * (kD * 2) + (kb * 4 + kg) * 16) : z;
+        }
+    }
 }
 
 // Dynamic LDS of a workgroup: the cross-wave combine area ([kWaves][G][kD] accumulators, then
@@ -519,17 +573,17 @@ __device__ __forceinline__ void stage_wave_state(const WaveState& st, float* lds
     }
 }
 
-// four dims of a final row (row = sequence * Hq + head)
+// four dims of a final row (row = sequence * Hq + head, of `dout` dims)
 __device__ __forceinline__ void store_final_quad(void* out_o, float* out_lse, bool out_bf16, long long row, int d,
-                                                 f32x4 o, float lse)
+                                                 f32x4 o, float lse, int dout = kD)
 {
     if (out_bf16) {
         uint2 pk;
         pk.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
         pk.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
-        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out_o) + row * kD + d) = pk;
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out_o) + row * dout + d) = pk;
     } else {
-        *reinterpret_cast<f32x4*>(static_cast<float*>(out_o) + row * kD + d) = o;
+        *reinterpret_cast<f32x4*>(static_cast<float*>(out_o) + row * dout + d) = o;
     }
     if (out_lse && d == 0) out_lse[row] = lse;
 }
@@ -559,13 +613,16 @@ __device__ __forceinline__ void store_shared4(float* base, int bytes, int off, f
 }
 
 // after a barrier: the states of waves w0 .. w1-1 merged with the log-sum-exp rule into four dims of one
-// head of the item's row, at position idx of the G x 32
+// head of the item's row, at position idx of the G x 32 (G = columns of the combine area).  `half`: position
+// idx of the (G / 2) x 16 - row idx / 16 of the kv-head pair, whose even-token sums are dims 0..63 of column
+// 2 row and whose odd-token sums are dims 64..127 of column 2 row + 1 (the two share their maximum).
+template <bool half = false>
 __device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, int w0, int w1, f32x4& o, float& lse)
 {
     const float* sh_acc = lds;
     const float* sh_m = lds + kWaves * G * kD;
     const float* sh_l = sh_m + kWaves * 16;
-    const int g = idx >> 5, d = (idx & 31) * 4;
+    const int g = half ? 2 * (idx >> 4) : idx >> 5, d = half ? (idx & 15) * 4 : (idx & 31) * 4;
     float mm = -INFINITY;
     for (int w = w0; w < w1; ++w) mm = fmaxf(mm, sh_m[w * 16 + g]);
     o = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -578,6 +635,10 @@ __device__ __forceinline__ void combine_quad(const float* lds, int G, int idx, i
             const float f = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
             ll += f * sh_l[w * 16 + g];
             oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g) * kD + combine_slot(g, d));
+            if (half) {
+                ll += f * sh_l[w * 16 + g + 1];
+                oo += f * *reinterpret_cast<const f32x4*>(sh_acc + (w * G + g + 1) * kD + combine_slot(g + 1, 64 + d));
+            }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = oo[i] / ll;
@@ -811,7 +872,7 @@ __device__ __forceinline__ void merge_job(MergeJob& j, const DecodeParams& p, in
 // after a barrier: the item's rows from the states of waves w0 .. w1-1, and their stores (only seq, chunk and
 // kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn.  The fold of rows
 // from other sources is the out-of-line merge's (one wave calls this then).
-template <bool can_fold>
+template <bool can_fold, bool half = false>
 __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const Item& it, const float* lds, int G,
                                                   int tid, int nthreads, int mode, MergeJob* job = nullptr,
                                                   int w0 = 0, int w1 = kWaves)
@@ -824,16 +885,20 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
     const bool final_row = mode == kRowFinal;
     // a final row is also kept as a partial one when the call has a single chunk slot and a partial buffer
     const bool partial_row = !final_row || p.max_chunks == 1;
-    const long long prow0 = ((long long)it.seq * p.max_chunks + chunk_index(it.chunk)) * p.hq + (long long)it.kvh * G;
-    const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
-    for (int idx = tid; idx < G * (kD / 4); idx += nthreads) {
-        const int g = idx >> 5, d = (idx & 31) * 4;
+    // `half`: the item's rows are the 2 G heads of a kv-head pair, 64 dims each, among 2 p.hq heads; its
+    // combine area has 4 G columns
+    constexpr int dout = half ? kD / 2 : kD;
+    const int heads = half ? 2 * G : G, hq = half ? 2 * p.hq : p.hq, cols = half ? 4 * G : G;
+    const long long prow0 = ((long long)it.seq * p.max_chunks + chunk_index(it.chunk)) * hq + (long long)it.kvh * heads;
+    const long long orow0 = (long long)it.seq * hq + (long long)it.kvh * heads;
+    for (int idx = tid; idx < heads * (dout / 4); idx += nthreads) {
+        const int g = half ? idx >> 4 : idx >> 5, d = half ? (idx & 15) * 4 : (idx & 31) * 4;
         f32x4 o;
         float lse;
-        combine_quad(lds, G, idx, w0, w1, o, lse);
+        combine_quad<half>(lds, cols, idx, w0, w1, o, lse);
         if (p.part_o && partial_row && lse != -INFINITY) {
-            if (mode == kRowShared) store_shared4(p.part_o + prow0 * kD, G * kD * 4, (g * kD + d) * 4, o);
-            else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * kD + d));
+            if (mode == kRowShared) store_shared4(p.part_o + prow0 * dout, heads * dout * 4, (g * dout + d) * 4, o);
+            else __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(p.part_o + (prow0 + g) * dout + d));
         }
         // 4 G bytes: a plain store, so that the L2 can fill the line; the slot of a row that went out as a
         // final row holds no partial
@@ -841,7 +906,7 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
             if (mode == kRowShared) __hip_atomic_store(p.part_lse + prow0 + g, lse, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             else p.part_lse[prow0 + g] = partial_row ? lse : -INFINITY;
         }
-        if (final_row) store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + g, d, o, lse);
+        if (final_row) store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + g, d, o, lse, dout);
     }
 }
 
@@ -849,22 +914,24 @@ __device__ __forceinline__ void combine_and_store(const DecodeParams& p, const I
 // the range is the sequence's whole (empty) range and the call writes final rows: O = 0 and LSE = -inf
 // (what other sources hold for such a sequence is the out-of-line merge's, see the persistent form).
 __device__ __forceinline__ void store_empty(const DecodeParams& p, int seq, int chunk, int head0, int heads,
-                                            int tid, int nthreads, bool final_here)
+                                            int tid, int nthreads, bool final_here, int hq, int dout)
 {
-    const long long prow0 = ((long long)seq * p.max_chunks + chunk) * p.hq + head0;
-    const long long orow0 = (long long)seq * p.hq + head0;
+    const long long prow0 = ((long long)seq * p.max_chunks + chunk) * hq + head0;
+    const long long orow0 = (long long)seq * hq + head0;
     if (p.part_lse)
         for (int h = tid; h < heads; h += nthreads) p.part_lse[prow0 + h] = -INFINITY;
     if (final_here) {
-        for (int idx = tid; idx < heads * (kD / 4); idx += nthreads)
-            store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + (idx >> 5), (idx & 31) * 4,
-                             f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY);
+        const int quads = dout / 4;
+        for (int idx = tid; idx < heads * quads; idx += nthreads)
+            store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + idx / quads, (idx % quads) * 4,
+                             f32x4{0.f, 0.f, 0.f, 0.f}, -INFINITY, dout);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // grid form
 // ---------------------------------------------------------------------------------------------------
+template <bool half>
 __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodeParams p, const int* __restrict__ block_table)
 {
     // the K staging areas and the combine area share the same LDS: the combine starts after a barrier
@@ -884,8 +951,9 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     if (p.seq_final && chunk == 0 && it.kvh == 0 && threadIdx.x == 0)
         p.seq_final[it.seq] = (p.out_o != nullptr && n_live <= 1) ? 1 : 0;
     if (it.ce <= it.cb) {
-        store_empty(p, it.seq, chunk, it.kvh * p.group, p.group, threadIdx.x, kThreads,
-                    p.out_o != nullptr && chunk == 0);
+        constexpr int per = half ? 2 : 1;                  // heads per kv head of the launch's geometry
+        store_empty(p, it.seq, chunk, it.kvh * p.group * per, p.group * per, threadIdx.x, kThreads,
+                    p.out_o != nullptr && chunk == 0, p.hq * per, kD / per);
         return;
     }
     finish_item(it, block_table, p.max_blocks);
@@ -893,21 +961,21 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     it.ds = kWaves;
     const float scale2 = p.sm_scale * kLog2e;
     u32x4 qb[4];
-    load_q(p, it, id.col, id.kg, qb);
+    load_q<half>(p, it, id.col, id.kg, qb);
     WaveState st;
     st.reset();
     StepRegs r;
     Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
     if (id.wave < it.n_steps) {
-        cur = step_pages(p, it, id.wave);
+        cur = step_pages<half>(p, it, id.wave);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
-    if (id.wave + kWaves < it.n_steps) second = step_pages(p, it, id.wave + kWaves);
-    run_item<false>(p, it, st, r, qb, id, scale2, cur, second, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
+    if (id.wave + kWaves < it.n_steps) second = step_pages<half>(p, it, id.wave + kWaves);
+    run_item<false, half>(p, it, st, r, qb, id, scale2, cur, second, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
     __syncthreads();
-    stage_wave_state(st, lds, p.group, id.wave, id.col, id.kg);
+    stage_wave_state(st, lds, half ? 4 * p.group : p.group, id.wave, id.col, id.kg);
     __syncthreads();
-    combine_and_store<false>(p, it, lds, p.group, threadIdx.x, kThreads, row_mode(p, n_live));
+    combine_and_store<false, half>(p, it, lds, p.group, threadIdx.x, kThreads, row_mode(p, n_live));
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1117,7 +1185,7 @@ constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming wav
 
 // `fused`: the launch may finish sequences by merging (p.fuse); the plain instance carries none of that code,
 // whose register needs change how the compiler schedules the streaming loop (2 % of the launch).
-template <bool fused>
+template <bool fused, bool half>
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
@@ -1128,7 +1196,8 @@ __device__ __forceinline__ void persistent_body(
     // non-empty chunks of the sequence) of the item (slot 0) or of each wave's item (seq < 0: the wave had none)
     __shared__ int sh_item[2][kItemWords];
     __shared__ MergeJob sh_job[kWaves];                    // the writer wave's jobs for the merge routine, per ticket
-    const size_t comb_bytes = combine_bytes(p.group);      // two combine areas, by ticket parity
+    const int comb_cols = half ? 4 * p.group : p.group;    // columns of the Q^T operand that are in use
+    const size_t comb_bytes = combine_bytes(comb_cols);    // two combine areas, by ticket parity
     char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
     char* const q_base = stage_base + kWaves * kStageBytes;          // [parity][wave] buffers of G rows
     const int q_bytes = p.group * kD * 2;
@@ -1143,7 +1212,8 @@ __device__ __forceinline__ void persistent_body(
     auto store_empty_share = [&] {
         auto empty_slot = [&](int seq, int chunk) {
             const bool final_here = p.out_o != nullptr && chunk == 0;
-            store_empty(p, seq, chunk, 0, p.hq, id.lane, kWave, final_here && !(fused && p.n_ext > 0));
+            store_empty(p, seq, chunk, 0, half ? 2 * p.hq : p.hq, id.lane, kWave, final_here && !(fused && p.n_ext > 0),
+                        half ? 2 * p.hq : p.hq, half ? kD / 2 : kD);
             if (fused && final_here && p.n_ext > 0) fold_rows_plain(p, seq, id.lane);
         };
         const unsigned n_empty = min(counts[1], total);
@@ -1219,8 +1289,8 @@ __device__ __forceinline__ void persistent_body(
                 const int mode = row_mode(p, chunk_live(done.chunk));
                 shared |= mode == kRowShared;
                 MergeJob* job = &sh_job[n_jobs];
-                if (grouped) combine_and_store<fused>(p, done, area, p.group, id.lane, kWave, mode, job, w, w + 1);
-                else combine_and_store<fused>(p, done, area, p.group, id.lane, kWave, mode, job);
+                if (grouped) combine_and_store<fused, half>(p, done, area, p.group, id.lane, kWave, mode, job, w, w + 1);
+                else combine_and_store<fused, half>(p, done, area, p.group, id.lane, kWave, mode, job);
                 if (fused && mode == kRowFinalFold) ++n_jobs;
             }
             if (fused && shared) {
@@ -1266,14 +1336,14 @@ __device__ __forceinline__ void persistent_body(
     StepRegs r;
     Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
     if (has_steps(it)) {
-        cur = step_pages(p, it, it.s0);
+        cur = step_pages<half>(p, it, it.s0);
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
-    if (it.s0 + it.ds < it.n_steps) second = step_pages(p, it, it.s0 + it.ds);
+    if (it.s0 + it.ds < it.n_steps) second = step_pages<half>(p, it, it.s0 + it.ds);
     OMNI_WAIT_VMCNT(16);                                   // Q is older than the 16 K/V requests
     lds_barrier();
     u32x4 qb[4];
-    read_q(q_buffer(0, it), p.group, id.col, id.kg, qb);
+    read_q<half>(q_buffer(0, it), p.group, id.col, id.kg, qb);
     WaveState st;
     st.reset();
 
@@ -1304,18 +1374,18 @@ __device__ __forceinline__ void persistent_body(
             has_next = tn < n_tickets;
             if (has_next) {
                 nx = ticket_item(p, entries, block_table, ts, tn, id.wave);
-                if (has_steps(nx)) tail = Tail{true, nx.kvh, step_pages(p, nx, nx.s0)};
+                if (has_steps(nx)) tail = Tail{true, nx.kvh, step_pages<half>(p, nx, nx.s0)};
                 // the table reads for the wave's second step of that item go out now as well: at the
                 // item's start they would be a cold round trip in front of its second request
                 next_second = Pages{-1, -1};
-                if (nx.s0 + nx.ds < nx.n_steps) next_second = step_pages(p, nx, nx.s0 + nx.ds);
+                if (nx.s0 + nx.ds < nx.n_steps) next_second = step_pages<half>(p, nx, nx.s0 + nx.ds);
                 q_coming = brings_q(nx);
             } else {
                 nx.n_steps = 0;
             }
         };
 
-        run_item<true>(p, it, st, r, qb, id, scale2, cur, second,
+        run_item<true, half>(p, it, st, r, qb, id, scale2, cur, second,
                  [&](bool before) {
                      if (threadIdx.x == 0 && late_draw) {
                          if (before) t1 = atomicAdd(ticket_counter, 1u);
@@ -1345,7 +1415,7 @@ __device__ __forceinline__ void persistent_body(
         // were; then the workgroup meets, with all those loads still in flight, and the writer wave takes
         // over
         float* const area = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + (k & 1) * comb_bytes);
-        stage_wave_state(st, area, p.group, id.wave, id.col, id.kg);
+        stage_wave_state(st, area, comb_cols, id.wave, id.col, id.kg);
         cur = tail.pages;
         second = next_second;
         if (tail.valid && !streamed) {
@@ -1366,7 +1436,7 @@ __device__ __forceinline__ void persistent_body(
         lds_barrier();
         if (!has_next) break;
         if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by ticket k+4
-        read_q(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
+        read_q<half>(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
         st.reset();
         it = nx;
     }
@@ -1376,12 +1446,12 @@ __device__ __forceinline__ void persistent_body(
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
-template <bool fused>
+template <bool fused, bool half>
 __global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
-    persistent_body<fused>(p, block_table, header, counts, entries, arrivals);
+    persistent_body<fused, half>(p, block_table, header, counts, entries, arrivals);
     if (threadIdx.x == 0) {
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
@@ -1402,10 +1472,13 @@ size_t lds_bytes(int group, bool persistent)
 
 }  // namespace
 
+// head_dim 64 runs as kv-head pairs (see the top of the file): an even number of kv heads, G <= 4
+bool decode_mfma_half(const DecodeParams& p) { return p.d == kD / 2; }
+
 bool decode_mfma_supports(const DecodeParams& p, bool bf16)
 {
-    return bf16 && p.d == kD && p.group <= 16 &&
-           (long long)p.batch * p.max_chunks * p.hkv <= 0x7fffffffLL;
+    const bool shape = (p.d == kD && p.group <= 16) || (p.d == kD / 2 && p.group <= 4 && p.hkv % 2 == 0);
+    return bf16 && shape && (long long)p.batch * p.max_chunks * p.hkv <= 0x7fffffffLL;
 }
 
 size_t decode_workspace_bytes(long long batch, long long max_chunks, long long hkv)
@@ -1467,17 +1540,22 @@ hipError_t device_facts(int& cus)
         f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
         const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
         if (f.status == hipSuccess) {
-            const void* forms[2] = {(const void*)decode_mfma_persistent_kernel<false>,
-                                    (const void*)decode_mfma_persistent_kernel<true>};
-            for (int i = 0; i < 2 && f.status == hipSuccess; ++i)
+            const void* forms[3] = {(const void*)decode_mfma_persistent_kernel<false, false>,
+                                    (const void*)decode_mfma_persistent_kernel<true, false>,
+                                    (const void*)decode_mfma_persistent_kernel<false, true>};
+            for (int i = 0; i < 3 && f.status == hipSuccess; ++i)
                 f.status = hipFuncSetAttribute(forms[i], hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
         }
-        if (f.status == hipSuccess && lds_g > 64 * 1024)
-            f.status = hipFuncSetAttribute((const void*)decode_mfma_grid_kernel,
+        if (f.status == hipSuccess && lds_g > 64 * 1024) {
+            f.status = hipFuncSetAttribute((const void*)decode_mfma_grid_kernel<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_g);
+            if (f.status == hipSuccess)
+                f.status = hipFuncSetAttribute((const void*)decode_mfma_grid_kernel<true>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_g);
+        }
         int per_cu = 0;
         if (f.status == hipSuccess)
-            f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel<true>,
+            f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel<true, false>,
                                                                     kPersistentThreads, lds_p);
         if (f.status == hipSuccess && (per_cu < 1 || f.cus < 1)) f.status = hipErrorLaunchOutOfResources;
         f.known = true;
@@ -1488,15 +1566,25 @@ hipError_t device_facts(int& cus)
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s)
+hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool planned, hipStream_t s)
 {
-    const size_t lds = lds_bytes(p.group, workspace != nullptr);
+    // head_dim 64: the kernels see kv-head pairs as kv heads of 128-wide rows, half as many of them and of
+    // the 256-byte query rows, and 4 G columns of the Q^T operand in use
+    const bool half = decode_mfma_half(given);
+    DecodeParams p = given;
+    if (half) {
+        p.hq = given.hq / 2;
+        p.hkv = given.hkv / 2;
+        if (p.fuse) return hipErrorInvalidValue;           // (the API layer does not let this through)
+    }
+    const size_t lds = lds_bytes(half ? 4 * p.group : p.group, workspace != nullptr);
     int cus = 0;
     hipError_t e = device_facts(cus);
     if (e != hipSuccess) return e;
     if (!workspace) {
         const unsigned grid = (unsigned)((long long)p.batch * p.max_chunks * p.hkv);
-        hipLaunchKernelGGL(decode_mfma_grid_kernel, dim3(grid), dim3(kThreads), lds, s, p, p.block_table);
+        if (half) hipLaunchKernelGGL(decode_mfma_grid_kernel<true>, dim3(grid), dim3(kThreads), lds, s, p, p.block_table);
+        else hipLaunchKernelGGL(decode_mfma_grid_kernel<false>, dim3(grid), dim3(kThreads), lds, s, p, p.block_table);
         return hipGetLastError();
     }
     unsigned* header = static_cast<unsigned*>(workspace);
@@ -1512,7 +1600,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool plann
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
-    auto kernel = p.fuse ? decode_mfma_persistent_kernel<true> : decode_mfma_persistent_kernel<false>;
+    auto kernel = half ? decode_mfma_persistent_kernel<false, true>
+                       : (p.fuse ? decode_mfma_persistent_kernel<true, false> : decode_mfma_persistent_kernel<false, false>);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p, p.block_table, header, header + 1,
                        entries, arrivals);
     return hipGetLastError();

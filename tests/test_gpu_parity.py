@@ -158,6 +158,42 @@ def test_head_layouts(kernel, shape, dtype):
     run_and_check(w, kernel)
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("shape", [(8, 8), (4, 2), (6, 2), (16, 4), (12, 4), (32, 8)])
+def test_head_dim_64_bf16(kernel, shape):
+    """bf16 head_dim 64 with an even number of kv heads and up to four query heads per kv head runs on the
+    matrix-core kernel as kv-head pairs (the automatic choice): ragged ranges that start past token 0,
+    chunked and unchunked, rows written as partials, as final fp32 rows and as final bf16 rows."""
+    hq, hkv = shape
+    rng = np.random.default_rng([67, hq, hkv])
+    lengths = rng.integers(1, 700, size=11)
+    lengths[:3] = [1, 16, 33]
+    begin = rng.integers(0, 2, size=11) * rng.integers(0, 30, size=11)
+    w = wl.make_generic(67 + hq, lengths + begin, hq, hkv, 64, dtype="bf16", ctx_begin=begin, pool_factor=1.4)
+    exp = expected_full(w, begin=w.calls[0].ctx_begin, end=w.calls[0].ctx_end)
+    if kernel[0] == binding.OMNI_KERNEL_AUTO:
+        dw = DeviceWorkload(w, workspace=kernel[1])
+        args = dw.decode_args(dw.calls[0], kernel[0], 0, False)
+        assert binding.omni_decode_kernel_name(args).startswith("decode_mfma")
+    run_and_check(w, kernel, expected=exp, out_dtype="f32")
+    run_and_check(w, kernel, expected=exp, out_dtype="bf16",
+                  tol=TOL["bf16"] + float(np.max(np.abs(exp[0]))) * 2.0 ** -9)
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 96, 8
+    (_, dw) = run_and_check(w, kernel, expected=exp)
+    # every partial row against the oracle's partial over the same chunk
+    c = w.calls[0]
+    po = dw.calls[0]["part_o"].cpu().numpy().astype(np.float64)
+    pl = dw.calls[0]["part_lse"].cpu().numpy().astype(np.float64)
+    for ci in range(c.max_chunks):
+        b = np.minimum(c.ctx_begin + ci * 96, c.ctx_end)
+        e = np.minimum(b + 96, c.ctx_end)
+        live = e > b
+        assert np.all(pl[~live, ci] == -np.inf)
+        if live.any():
+            exp_o, exp_l = expected_full(w, b, e)
+            check(po[live, ci], pl[live, ci], exp_o[live], exp_l[live], 2e-3, "chunk %d" % ci)
+
+
 # ---------------------------------------------------------------------------
 # edge cases
 # ---------------------------------------------------------------------------
