@@ -61,19 +61,24 @@ def measured_traffic(workload_name: str):
     return t.get("bytes_per_launch", {}).get(workload_name)
 
 
-def algorithmic_bytes(w) -> int:
+def algorithmic_bytes(w, final_rows: bool) -> int:
     """Bytes one pass of the decode-attention calls must move: the KV of every attended token, its share of
-    the block table (4 bytes per 16-token page), q, and one output row (partial or final) per non-empty chunk."""
+    the block table (4 bytes per 16-token page), q, and one output row per non-empty chunk: an fp32 partial
+    row with its LSE, or, where the call writes final rows, the row in the output type with its LSE for a
+    sequence that has a single non-empty chunk and no rows from elsewhere."""
     total = w.kv_bytes()
+    out_bytes = 2 if w.out_dtype == "bf16" else 4
+    has_ext = np.zeros(w.batch, dtype=bool)            # sequences with rows computed elsewhere are never final
+    if w.ext_ranges is not None:
+        has_ext = np.array([len(rs) > 0 for rs in w.ext_ranges])
     for c in w.calls:
         tok = np.maximum(c.ctx_end.astype(np.int64) - c.ctx_begin, 0)
         total += int(((tok + w.block_size - 1) // w.block_size).sum()) * 4
         total += w.batch * w.num_q_heads * w.head_dim * w.elem_bytes
-        if c.chunk_tokens:
-            n_part = int(((tok + c.chunk_tokens - 1) // c.chunk_tokens).sum())
-        else:
-            n_part = int((tok > 0).sum())
-        total += n_part * w.num_q_heads * (w.head_dim + 1) * 4
+        n_chunks = (tok + c.chunk_tokens - 1) // c.chunk_tokens if c.chunk_tokens else (tok > 0).astype(np.int64)
+        n_final = int(((n_chunks == 1) & ~has_ext).sum()) if final_rows else 0
+        total += (int(n_chunks.sum()) - n_final) * w.num_q_heads * (w.head_dim + 1) * 4
+        total += n_final * w.num_q_heads * (w.head_dim * out_bytes + 4)
     return total
 
 
@@ -128,7 +133,7 @@ def run_workload(name, steps, warmup, pools, kernel, cores):
 
     w, dw, host_producer = make_device_workload(name, cores, pools)
     kv_bytes = w.kv_bytes()
-    alg_bytes = algorithmic_bytes(w)
+    alg_bytes = algorithmic_bytes(w, dw.mode == "final")
     n_calls = len(w.calls)
 
     # One step = work list + decode attention (the dominant kernel, bracketed by events on its own stream) +

@@ -148,13 +148,14 @@ typedef struct {
     /* non-zero: the workspace already holds the work list of exactly these ranges and this
      * chunking, written by omni_decode_plan (or by an earlier call with the same ranges): the
      * list is reused instead of rebuilt.  The list depends only on batch, ctx_begin, ctx_end,
-     * max_blocks_per_seq, chunk_tokens, max_chunks and num_kv_heads, so one plan serves the
-     * attention calls of every layer of a decoding iteration.                                 */
+     * max_blocks_per_seq, chunk_tokens, max_chunks and num_kv_heads (and, if ext_srcs are named
+     * without fuse_merge, on which sequences have rows there), so one plan serves the attention
+     * calls of every layer of a decoding iteration.                                           */
     int32_t  workspace_planned;
     /* optional [batch] int32 output: 1 where this call wrote the sequence's final row to out_o /
      * out_lse, 0 where its partial rows still have to be merged (omni_merge_partials_masked takes
-     * the array as its skip list).  Required when out_o is given with max_chunks > 1 and
-     * fuse_merge == 0.                                                                         */
+     * the array as its skip list).  Required (as are the partial buffers) when out_o is given,
+     * fuse_merge == 0 and max_chunks > 1 or ext_srcs are named.                                */
     int32_t* seq_final;
     /* non-zero: every sequence's final row comes out of this call (persistent form of the
      * matrix-core kernel only: a workspace is required, else UNSUPPORTED; out_o is required).
@@ -164,7 +165,12 @@ typedef struct {
      * ext_srcs[0 .. n_ext_srcs) (host array of up to 3 sources, copied during the call; NULL / 0 =
      * none) are rows computed elsewhere for these sequences - the attention rows that come back
      * through the output queue - and are folded into the final rows by the same rule, so that a
-     * hybrid batch needs no separate merge launch.                                             */
+     * hybrid batch needs no separate merge launch.
+     * With fuse_merge == 0 and out_o given, ext_srcs only tell the call which sequences have rows
+     * elsewhere (their row counts are read, their O and LSE are not): such a sequence is never
+     * finished here - it writes its partial row and seq_final 0 even if its range fits one chunk -
+     * so that the merge finds every part of it.  A planned work list records this: plan and call
+     * must name the same sources, and the list holds while the row counts do.                  */
     int32_t  fuse_merge;
     const struct omni_partial_src_s* ext_srcs;
     int32_t  n_ext_srcs;

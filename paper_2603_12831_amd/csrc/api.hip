@@ -37,10 +37,10 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
         // without partial buffers every row must be a final row: a single chunk slot
         if (!partials && !(a->out_o && a->max_chunks == 1)) return OMNI_ERR_NULL;
         // final rows of part of the batch only: the caller must be told which
-        if (a->out_o && a->max_chunks > 1 && !a->fuse_merge && !a->seq_final) return OMNI_ERR_NULL;
+        const bool some_left = a->max_chunks > 1 || a->n_ext_srcs > 0;
+        if (a->out_o && some_left && !a->fuse_merge && (!a->seq_final || !partials)) return OMNI_ERR_NULL;
         if (a->fuse_merge && !a->out_o) return OMNI_ERR_NULL;
         if (a->n_ext_srcs > 0) {
-            if (!a->fuse_merge) return OMNI_ERR_SHAPE;
             if (!a->ext_srcs) return OMNI_ERR_NULL;
             for (int i = 0; i < a->n_ext_srcs; ++i) {
                 if (!a->ext_srcs[i].o || !a->ext_srcs[i].lse) return OMNI_ERR_NULL;
@@ -66,8 +66,9 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
     p.out_bf16 = a->out_dtype == OMNI_BF16;
     p.out_lse = p.out_o ? a->out_lse : nullptr;
     p.seq_final = need_outputs ? a->seq_final : nullptr;
-    p.fuse = (need_outputs && a->fuse_merge) ? 1 : 0;
-    p.n_ext = p.fuse ? a->n_ext_srcs : 0;
+    // (the work list records which sequences the call can finish, so the plan call sees these as well)
+    p.fuse = (a->out_o && a->fuse_merge) ? 1 : 0;
+    p.n_ext = (a->out_o && a->ext_srcs) ? a->n_ext_srcs : 0;
     for (int i = 0; i < 3; ++i)
         p.ext[i] = i < p.n_ext ? a->ext_srcs[i] : omni_partial_src{nullptr, nullptr, nullptr, 0};
     return OMNI_OK;

@@ -598,7 +598,7 @@ __device__ __forceinline__ int row_mode(const DecodeParams& p, int n_live)
 {
     if (p.out_o == nullptr) return kRowPartial;
     if (n_live > 1) return p.fuse ? kRowShared : kRowPartial;
-    return p.n_ext > 0 ? kRowFinalFold : kRowFinal;
+    return (p.fuse && p.n_ext > 0) ? kRowFinalFold : kRowFinal;
 }
 
 // Partial rows that cross from one workgroup to another inside a launch are stored and loaded at device
@@ -946,14 +946,14 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
     int b, e;
     seq_range(p, it.seq, b, e);
     chunk_range(p, b, e, chunk, it.cb, it.ce);
-    const int n_live = live_chunks(p, b, e);
+    const int n_live = seq_parts(p, it.seq, b, e);
     it.chunk = pack_chunk(chunk, n_live);
     if (p.seq_final && chunk == 0 && it.kvh == 0 && threadIdx.x == 0)
         p.seq_final[it.seq] = (p.out_o != nullptr && n_live <= 1) ? 1 : 0;
     if (it.ce <= it.cb) {
         constexpr int per = half ? 2 : 1;                  // heads per kv head of the launch's geometry
         store_empty(p, it.seq, chunk, it.kvh * p.group * per, p.group * per, threadIdx.x, kThreads,
-                    p.out_o != nullptr && chunk == 0, p.hq * per, kD / per);
+                    p.out_o != nullptr && chunk == 0 && n_live <= 1, p.hq * per, kD / per);
         return;
     }
     finish_item(it, block_table, p.max_blocks);
@@ -1070,7 +1070,7 @@ __global__ __launch_bounds__(1024) void decode_list_kernel(DecodeParams p, unsig
         if (cached) { b = sh_b[seq]; en = sh_e[seq]; }
         else seq_range(p, seq, b, en);
         chunk_range(p, b, en, chunk, cb, ce);
-        return live_chunks(p, b, en);
+        return seq_parts(p, seq, b, en);
     };
     for (int i = threadIdx.x; i < p.batch * p.hkv; i += blockDim.x) arrivals[i] = 0;
     for (int base = 0; base < total; base += blockDim.x) {
@@ -1171,7 +1171,7 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     // worst that can come of it, never an access outside the table or the output buffers.
     const int cap = p.max_blocks * kBlockSize;
     it.seq = min(max(w.seq, 0), p.batch - 1);
-    it.chunk = pack_chunk(min(chunk_index(w.chunk), p.max_chunks - 1), min(max(chunk_live(w.chunk), 1), p.max_chunks));
+    it.chunk = pack_chunk(min(chunk_index(w.chunk), p.max_chunks - 1), min(max(chunk_live(w.chunk), 1), p.max_chunks + 1 - p.fuse));  // (parts: chunks, + 1 for rows from elsewhere)
     it.cb = min(max(w.cb, 0), cap - 1);
     it.ce = min(max(w.ce, it.cb + 1), cap);
     finish_item(it, block_table, p.max_blocks);
@@ -1210,8 +1210,8 @@ __device__ __forceinline__ void persistent_body(
     // rows of empty chunks: LSE = -inf, and the final row of a sequence whose whole range is empty (stores
     // only, shared out over the resident workgroups); and which sequences this call finishes
     auto store_empty_share = [&] {
-        auto empty_slot = [&](int seq, int chunk) {
-            const bool final_here = p.out_o != nullptr && chunk == 0;
+        auto empty_slot = [&](int seq, int chunk, int n_parts) {
+            const bool final_here = p.out_o != nullptr && chunk == 0 && n_parts <= 1;
             store_empty(p, seq, chunk, 0, half ? 2 * p.hq : p.hq, id.lane, kWave, final_here && !(fused && p.n_ext > 0),
                         half ? 2 * p.hq : p.hq, half ? kD / 2 : kD);
             if (fused && final_here && p.n_ext > 0) fold_rows_plain(p, seq, id.lane);
@@ -1219,13 +1219,14 @@ __device__ __forceinline__ void persistent_body(
         const unsigned n_empty = min(counts[1], total);
         for (unsigned i = blockIdx.x; i < n_empty; i += gridDim.x) {
             const WorkEntry w = load_invariant(entries + (total - 1u - i));
-            empty_slot(uniform(min(max(w.seq, 0), p.batch - 1)), uniform(min(chunk_index(w.chunk), p.max_chunks - 1)));
+            empty_slot(uniform(min(max(w.seq, 0), p.batch - 1)), uniform(min(chunk_index(w.chunk), p.max_chunks - 1)),
+                       uniform(chunk_live(w.chunk)));
         }
         if (p.seq_final) {
             for (int i = blockIdx.x * kWave + id.lane; i < p.batch; i += gridDim.x * kWave) {
                 int b, e;
                 seq_range(p, i, b, e);
-                p.seq_final[i] = (p.out_o != nullptr && (p.fuse || live_chunks(p, b, e) <= 1)) ? 1 : 0;
+                p.seq_final[i] = (p.out_o != nullptr && (p.fuse || seq_parts(p, i, b, e) <= 1)) ? 1 : 0;
             }
         }
     };

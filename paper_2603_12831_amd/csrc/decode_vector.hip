@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
     seq_range(p, seq, b, e);
     chunk_range(p, b, e, chunk, cb, ce);
     // a sequence with at most one non-empty chunk (chunk 0) gets its final row from this kernel
-    const bool seq_direct = p.out_o != nullptr && live_chunks(p, b, e) <= 1;
+    const bool seq_direct = p.out_o != nullptr && seq_parts(p, seq, b, e) <= 1;
     if (p.seq_final && blockIdx.x == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
 
     // bf16 inputs (tolerance 2e-3): logits in the log2 domain and the hardware's exp2 / log2; fp32 inputs

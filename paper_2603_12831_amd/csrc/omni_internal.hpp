@@ -111,6 +111,25 @@ __device__ __forceinline__ int live_chunks(const DecodeParams& p, int b, int e)
     return n < (unsigned)p.max_chunks ? (int)n : p.max_chunks;
 }
 
+// What a sequence's final row has to be put together from, as far as this call can tell: its non-empty
+// chunks, and - in a call that is told of rows computed elsewhere but does not fold them in itself - one
+// more part where the sequence has such rows (then at least two, so that the call never takes the row for
+// finished).  A sequence of at most one part gets its final row from the call.
+__device__ __forceinline__ int seq_parts(const DecodeParams& p, int seq, int b, int e)
+{
+    int n = live_chunks(p, b, e);
+    if (!p.fuse && p.n_ext > 0) {
+        bool rows = false;
+        for (int s = 0; s < p.n_ext; ++s) {
+            int r0, r1;
+            src_rows(p.ext[s], seq, r0, r1);
+            rows |= r1 > r0;
+        }
+        if (rows) n = (n > 1 ? n : 1) + 1;
+    }
+    return n;
+}
+
 // ---- launchers (each defined beside its kernel) ---------------------------
 hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s);

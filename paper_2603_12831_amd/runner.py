@@ -92,7 +92,7 @@ class DeviceWorkload:
             out_o=self.out_o if final else None, out_lse=self.out_lse if final else None,
             kernel=kernel, workspace=c["workspace"], workspace_planned=planned,
             seq_final=self.seq_final if self.mode != "merge" else None, fuse_merge=self.mode == "fused",
-            ext_srcs=[self.ext] if (self.mode == "fused" and self.ext is not None) else None)
+            ext_srcs=[self.ext] if (self.mode != "merge" and self.ext is not None) else None)
 
     def plan(self, stream=None):
         """Build the work list of every decode call once (it can then serve many attention passes)."""

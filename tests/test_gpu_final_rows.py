@@ -174,6 +174,53 @@ def test_fused_form_folds_rows_computed_elsewhere():
     check(o_e, l_e, exp2[0], exp2[1], TOL["bf16"], "fused hybrid, empty resident ranges")
 
 
+@pytest.mark.parametrize("kernel", KERNELS + [(binding.OMNI_KERNEL_VECTOR, False)])
+def test_final_rows_leave_sequences_with_rows_elsewhere_to_the_merge(kernel):
+    """Hybrid batch with the sources named but not folded in: the call finishes the sequences that have
+    neither a second chunk nor rows elsewhere, says so in seq_final, and the masked merge puts the others
+    together from every part - also where the resident range is a single chunk, or empty."""
+    w = wl.make_cfg4(n_ls=5, n_be=20, ls_lo=20, ls_hi=600, be_lo=300, be_hi=900, tail_lo=5, tail_hi=200)
+    ext = ext_partials_from_oracle(w)
+    has_ext = np.array([len(rs) > 0 for rs in w.ext_ranges])
+    exp = expected_full(w)
+    for chunk_tokens, max_chunks in ((0, 1), (64, 12)):
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk_tokens, max_chunks
+        o_m, l_m, _ = run_mode(w, "merge", kernel, ext=ext)
+        o_f, l_f, dw = run_mode(w, "final", kernel, ext=ext, passes=2)
+        final = (live_chunk_count(w) <= 1) & ~has_ext
+        assert final.any() and not final.all()
+        assert np.array_equal(dw.seq_final.cpu().numpy(), final.astype(np.int32))
+        assert np.array_equal(o_f, o_m) and np.array_equal(l_f, l_m)
+        check(o_f, l_f, exp[0], exp[1], TOL["bf16"], "final rows, hybrid batch, chunk %d" % chunk_tokens)
+    # two best-effort rows without resident tokens (their rows elsewhere are all there is), one
+    # latency-sensitive row without any context at all (finished here: O = 0, LSE = -inf)
+    w.calls[0].chunk_tokens, w.calls[0].max_chunks = 0, 1
+    n_ls = w.meta["n_ls"]
+    end = w.calls[0].ctx_end.copy()
+    for i in (n_ls + 1, n_ls + 4):
+        end[i] = w.calls[0].ctx_begin[i]
+    end[2] = 0
+    w.calls[0].ctx_end = end
+    exp2 = expected_full(w, begin=np.zeros_like(end), end=end)
+    o_e, l_e, dw = run_mode(w, "final", kernel, ext=ext)
+    fin = dw.seq_final.cpu().numpy()
+    assert fin[2] == 1 and fin[n_ls + 1] == 0 and fin[n_ls + 4] == 0
+    assert np.all(o_e[2] == 0) and np.all(l_e[2] == -np.inf)
+    check(o_e, l_e, exp2[0], exp2[1], TOL["bf16"], "final rows, hybrid batch, empty resident ranges")
+
+
+def test_final_rows_with_sources_need_seq_final_and_partials():
+    w = wl.make_cfg4(n_ls=3, n_be=6, ls_lo=20, ls_hi=100, be_lo=300, be_hi=400, tail_lo=5, tail_hi=50)
+    ext = ext_partials_from_oracle(w)
+    dw = DeviceWorkload(w, out_dtype="f32", ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2], mode="final")
+    args = dw.decode_args(dw.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    args.seq_final = None
+    assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_NULL
+    args = dw.decode_args(dw.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    args.part_o, args.part_lse = None, None
+    assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_NULL
+
+
 def test_fused_form_needs_the_persistent_kernel():
     w = mixed_batch(seed=75)
     dw = DeviceWorkload(w, out_dtype="f32", workspace=False, mode="fused")
@@ -212,8 +259,23 @@ def test_fused_step_in_a_graph_replays_exactly():
 
 
 @pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_full_size_final_rows(name):
+    """The full-size configurations as bench.py times them: final rows from the attention call where it can
+    finish a sequence, the masked merge for the rest, work list rebuilt by the call."""
+    w = wl.MAKERS[name](workers=THREADS)
+    ext = ext_partials_from_oracle(w) if w.ext_ranges is not None else None
+    o, l, dw = run_mode(w, "final", ext=ext, passes=2)
+    exp = expected_full(w)
+    eo, el = check(o, l, exp[0], exp[1], 2e-3, name + " final rows")
+    fin = int(dw.seq_final.sum().item())
+    print("%s final rows: %d of %d sequences finished by the call, max abs err O %.3g LSE %.3g"
+          % (name, fin, w.batch, eo, el))
+    assert fin == {"cfg3": 82, "cfg4": 32, "cfg5": 0}[name]
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_full_size_fused(name):
-    """The full-size configurations through the fused form (what bench.py times)."""
+    """The full-size configurations through the fused form."""
     w = wl.MAKERS[name](workers=THREADS)
     ext = ext_partials_from_oracle(w) if w.ext_ranges is not None else None
     o, l, dw = run_mode(w, "fused", ext=ext, passes=2)
