@@ -126,8 +126,10 @@ def host_stream_reference(w, cores, host_kv, producer_seconds):
     return {"host_stream_read_GBps": rate, "frac_of_host_stream_read": (host_kv / producer_seconds / 1e9) / rate}
 
 
-def run_workload(name, steps, warmup, pools, kernel, cores):
-    """Times one workload; returns (its report, the workload, the device buffers)."""
+def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
+    """Times one workload; returns (its report, the workload, the device buffers).  `min_seconds`: take more
+    than `steps` steps (and warm-up steps) if that many would fill less than this much time - a timed region
+    of a few milliseconds mostly measures its own two ends."""
     import torch
     from paper_2603_12831_amd import binding
 
@@ -154,8 +156,16 @@ def run_workload(name, steps, warmup, pools, kernel, cores):
     spin_bytes = min(dw.k_pools[0].numel() * dw.k_pools[0].element_size(), 1 << 30)
     for _ in range(int(0.05 / (spin_bytes / 6e12)) + 1):
         binding.omni_debug_stream_read(dw.k_pools[0], sink, spin_bytes)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     for i in range(warmup):
         step(i)
+    torch.cuda.synchronize()
+    if min_seconds > 0.0 and warmup > 0:
+        est = (time.perf_counter() - t0) / warmup
+        steps = max(steps, int(min_seconds / est))
+        for i in range(int(0.4 * min_seconds / est)):
+            step(i)
     # events bracket the dominant kernel on every 4th timed step (each record costs a few microseconds of
     # stream time, which would otherwise be charged to every step)
     ev = {i: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -187,7 +197,7 @@ def run_workload(name, steps, warmup, pools, kernel, cores):
         "step_ms_median": per_step[len(per_step) // 2], "step_ms_min": per_step[0],
         "merged_tokens_per_s": w.batch / (step_ms * 1e-3),
         "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,
-        "kv_bytes_per_step": kv_bytes, "pool_copies_rotated": pools, "final_rows": dw.mode,
+        "kv_bytes_per_step": kv_bytes, "pool_copies_rotated": pools, "final_rows": dw.mode, "steps": steps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(w.name),
                      "kernel": binding.omni_decode_kernel_name(args0),
@@ -327,8 +337,8 @@ def main() -> int:
         for name in OTHER_WORKLOADS:
             if name == args.workload:
                 continue
-            rep, wo, dwo = run_workload(name, n_other, max(3, min(args.warmup, 10)), pools_for(name), args.kernel, cores)
-            rep["steps"] = n_other
+            rep, wo, dwo = run_workload(name, n_other, max(3, min(args.warmup, 10)), pools_for(name), args.kernel, cores,
+                                        min_seconds=0.05)
             out["workloads"][wo.name] = rep
             del dwo, wo
             torch.cuda.empty_cache()

@@ -338,6 +338,29 @@ def omni_merge_partials_masked(batch: int, num_q_heads: int, head_dim: int, srcs
     return st
 
 
+class PreparedMerge:
+    """A merge call with its arguments marshalled once (a step loop then pays one foreign call per merge):
+    `run(stream)` calls omni_merge_partials_masked (skip may be None) on the same buffers every time."""
+
+    def __init__(self, batch: int, num_q_heads: int, head_dim: int, srcs: Sequence[PartialSrc], skip, out_o,
+                 out_lse=None):
+        if out_o.numel() != batch * num_q_heads * head_dim:
+            raise ValueError("out_o has the wrong size")
+        if skip is not None and skip.numel() != batch:
+            raise ValueError("skip must have one entry per sequence")
+        self._keep = (list(srcs), skip, out_o, out_lse)        # the tensors behind the raw pointers
+        self._fn = load_library().omni_merge_partials_masked
+        self._argv = (batch, num_q_heads, head_dim, make_partial_srcs(srcs, batch, num_q_heads, head_dim), len(srcs),
+                      _dev_ptr(skip, "skip", torch.int32), _dev_ptr(out_o, "out_o"), _dtype_code(out_o, "out_o"),
+                      _dev_ptr(out_lse, "out_lse", torch.float32))
+
+    def run(self, stream=None, check: bool = True) -> int:
+        st = self._fn(*self._argv, _stream_ptr(stream))
+        if check and st != OMNI_OK:
+            raise OmniError(st, "omni_merge_partials_masked")
+        return st
+
+
 def omni_debug_gather_kv(args: omni_decode_args, seq: int, k_out, v_out, stream=None, check: bool = True) -> int:
     st = load_library().omni_debug_gather_kv(ctypes.byref(args), int(seq), _dev_ptr(k_out, "k_out"),
                                              _dev_ptr(v_out, "v_out"), _stream_ptr(stream))

@@ -70,6 +70,7 @@ class DeviceWorkload:
                                  device=self.device)
         self.out_lse = torch.empty((B, Hq), dtype=torch.float32, device=self.device)
         self.seq_final = torch.zeros(B, dtype=torch.int32, device=self.device)
+        self._arg_cache, self._merge_call = {}, None
         # a single one-chunk call with nothing else to merge writes the final rows itself
         self.direct = len(self.calls) == 1 and self.calls[0]["max_chunks"] == 1 and self.ext is None
         if self.direct:
@@ -94,16 +95,24 @@ class DeviceWorkload:
             seq_final=self.seq_final if self.mode != "merge" else None, fuse_merge=self.mode == "fused",
             ext_srcs=[self.ext] if (self.mode != "merge" and self.ext is not None) else None)
 
+    def _args(self, i: int, kernel: int, pool: int, planned: bool):
+        """decode_args of call i, marshalled once per combination (the step loops call this every step)."""
+        key = (i, kernel, pool, planned, self.mode, id(self.ext))
+        a = self._arg_cache.get(key)
+        if a is None:
+            a = self._arg_cache[key] = self.decode_args(self.calls[i], kernel, pool, planned)
+        return a
+
     def plan(self, stream=None):
         """Build the work list of every decode call once (it can then serve many attention passes)."""
-        for c in self.calls:
+        for i, c in enumerate(self.calls):
             if c["workspace"] is not None:
-                binding.omni_decode_plan(self.decode_args(c, binding.OMNI_KERNEL_AUTO, 0, False), stream)
+                binding.omni_decode_plan(self._args(i, binding.OMNI_KERNEL_AUTO, 0, False), stream)
 
     def run_attention(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None,
                       planned: bool = False):
-        for c in self.calls:
-            binding.omni_paged_decode_attn_raw(self.decode_args(c, kernel, pool, planned), stream)
+        for i in range(len(self.calls)):
+            binding.omni_paged_decode_attn_raw(self._args(i, kernel, pool, planned), stream)
 
     def merge_sources(self) -> List:
         srcs = [self.ext] if self.ext is not None else []
@@ -113,13 +122,13 @@ class DeviceWorkload:
     def run_merge(self, stream=None):
         if self.direct or self.mode == "fused":
             return
-        w = self.w
-        if self.mode == "final":
-            binding.omni_merge_partials_masked(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(),
-                                               self.seq_final, self.out_o, self.out_lse, stream=stream)
-        else:
-            binding.omni_merge_partials(w.batch, w.num_q_heads, w.head_dim, self.merge_sources(), self.out_o,
-                                        self.out_lse, stream=stream)
+        key = (self.mode, id(self.ext))
+        if self._merge_call is None or self._merge_call[0] != key:
+            w = self.w
+            self._merge_call = (key, binding.PreparedMerge(
+                w.batch, w.num_q_heads, w.head_dim, self.merge_sources(),
+                self.seq_final if self.mode == "final" else None, self.out_o, self.out_lse))
+        self._merge_call[1].run(stream)
 
     def run(self, kernel: int = binding.OMNI_KERNEL_AUTO, pool: int = 0, stream=None):
         """One pass of the whole hot path: every decode call, then the merge."""
