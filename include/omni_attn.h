@@ -405,6 +405,21 @@ omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_
 omni_status omni_debug_host_stream_read(const void* src, size_t bytes, int32_t n_threads, uint64_t* sink);
 
 /*
+ * Where the time of a persistent launch goes.  omni_debug_decode_timeline is omni_paged_decode_attn through
+ * an instance of the persistent matrix-core kernel that also stamps a constant-rate clock (100 MHz, the same
+ * for every workgroup) into `stamps` (device, n_words 64-bit words, zeroed by the caller): per workgroup w,
+ * words_per_workgroup words from stamps[w * words_per_workgroup]: [0] start, [1] first query rows in LDS,
+ * [2] streaming waves done, [3] the storing wave done, [4] tickets taken, [5] 32-token steps of wave 0,
+ * [8 + k] the workgroup's meeting after its k-th ticket (the first words_per_workgroup - 8 tickets).  A
+ * workgroup without work stamps [0] only.  omni_debug_decode_timeline_shape tells how many workgroups a
+ * launch on the current device has and how many words each writes.  Outputs are those of the plain call.
+ * Errors: as omni_paged_decode_attn; UNSUPPORTED unless the call runs the plain persistent form at head_dim
+ * 128 (workspace given, fuse_merge 0); SHAPE if n_words is too small.
+ */
+omni_status omni_debug_decode_timeline_shape(int32_t* n_workgroups, int32_t* words_per_workgroup);
+omni_status omni_debug_decode_timeline(const omni_decode_args* a, uint64_t* stamps, uint64_t n_words, void* hip_stream);
+
+/*
  * Test aids for the persistent form's work list (host only, no GPU call; they run the functions the kernels
  * use).  omni_debug_sort_bin: the sort key (0 .. 255, smaller = earlier in the list) of a non-empty range of
  * `tokens` tokens in a call with `chunk_tokens` (0 = unchunked); 256 for tokens <= 0.

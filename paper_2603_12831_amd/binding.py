@@ -28,7 +28,8 @@ EXPORTS = ("omni_paged_decode_attn", "omni_paged_decode_attn_static", "omni_deco
            "omni_debug_host_stream_read",
            "omni_kv_append", "omni_kv_gather_pages", "omni_kv_scatter_pages",
            "omni_queue_push", "omni_queue_pop", "omni_csr_from_tags", "omni_residual_save", "omni_residual_load",
-           "omni_host_partial_attn", "omni_debug_sort_bin", "omni_debug_ticket_map")
+           "omni_host_partial_attn", "omni_debug_sort_bin", "omni_debug_ticket_map",
+           "omni_debug_decode_timeline_shape", "omni_debug_decode_timeline")
 
 
 class OmniError(RuntimeError):
@@ -130,6 +131,10 @@ def load_library() -> ctypes.CDLL:
         lib.omni_debug_ticket_map.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int32, ctypes.c_uint32, vp,
                                               ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32)]
         lib.omni_debug_ticket_map.restype = ctypes.c_int
+        lib.omni_debug_decode_timeline_shape.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        lib.omni_debug_decode_timeline_shape.restype = ctypes.c_int
+        lib.omni_debug_decode_timeline.argtypes = [ctypes.POINTER(omni_decode_args), vp, ctypes.c_uint64, vp]
+        lib.omni_debug_decode_timeline.restype = ctypes.c_int
         qp = ctypes.POINTER(omni_queue)
         lib.omni_queue_push.argtypes = [qp, vp, vp, ctypes.c_int32, vp, vp]
         lib.omni_queue_push.restype = ctypes.c_int
@@ -359,6 +364,24 @@ class PreparedMerge:
         if check and st != OMNI_OK:
             raise OmniError(st, "omni_merge_partials_masked")
         return st
+
+
+def omni_debug_decode_timeline_shape():
+    """(workgroups of a persistent launch on the current device, 64-bit stamp words per workgroup)"""
+    n, w = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = load_library().omni_debug_decode_timeline_shape(ctypes.byref(n), ctypes.byref(w))
+    if st != OMNI_OK:
+        raise OmniError(st, "omni_debug_decode_timeline_shape")
+    return n.value, w.value
+
+
+def omni_debug_decode_timeline(args: omni_decode_args, stamps, stream=None, check: bool = True) -> int:
+    """The decode call through the time-stamping kernel instance; stamps: zeroed int64 device tensor."""
+    st = load_library().omni_debug_decode_timeline(ctypes.byref(args), _dev_ptr(stamps, "stamps", torch.int64),
+                                                   stamps.numel(), _stream_ptr(stream))
+    if check and st != OMNI_OK:
+        raise OmniError(st, "omni_debug_decode_timeline")
+    return st
 
 
 def omni_debug_gather_kv(args: omni_decode_args, seq: int, k_out, v_out, stream=None, check: bool = True) -> int:

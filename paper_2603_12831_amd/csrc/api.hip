@@ -66,6 +66,7 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
     p.out_bf16 = a->out_dtype == OMNI_BF16;
     p.out_lse = p.out_o ? a->out_lse : nullptr;
     p.seq_final = need_outputs ? a->seq_final : nullptr;
+    p.stamps = nullptr;
     // (the work list records which sequences the call can finish, so the plan call sees these as well)
     p.fuse = (a->out_o && a->fuse_merge) ? 1 : 0;
     p.n_ext = (a->out_o && a->ext_srcs) ? a->n_ext_srcs : 0;
@@ -76,11 +77,13 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
 
 // The decode call behind both of its entry points: `ws` / `ws_bytes` is the work-list scratch to use
 // (the caller's workspace, or the library's own array), `planned` whether it already holds the list.
-omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_bytes, bool planned, void* hip_stream)
+omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_bytes, bool planned, void* hip_stream,
+                        unsigned long long* stamps = nullptr)
 {
     DecodeParams p;
     omni_status st = flatten(a, p, true);
     if (st != OMNI_OK) return st;
+    p.stamps = stamps;
     if (a->kernel != OMNI_KERNEL_AUTO && a->kernel != OMNI_KERNEL_VECTOR && a->kernel != OMNI_KERNEL_MFMA)
         return OMNI_ERR_SHAPE;
     if (p.batch == 0) return OMNI_OK;
@@ -96,6 +99,8 @@ omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_b
     }
     // only the persistent form finishes every sequence, and only at head_dim 128
     if (p.fuse && (!ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
+    // the time-stamping instance is one of the plain persistent form at head_dim 128
+    if (p.stamps && (!mfma || !ws || p.d != 128 || p.fuse)) return OMNI_ERR_UNSUPPORTED;
     hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
@@ -385,6 +390,27 @@ omni_status omni_debug_copy(void* dst, const void* src, size_t bytes, void* hip_
 int32_t omni_debug_sort_bin(int32_t tokens, int32_t chunk_tokens)
 {
     return omni::decode_list_sort_bin(tokens, chunk_tokens);
+}
+
+omni_status omni_debug_decode_timeline_shape(int32_t* n_workgroups, int32_t* words_per_workgroup)
+{
+    if (!n_workgroups || !words_per_workgroup) return OMNI_ERR_NULL;
+    int n = 0, w = 0;
+    if (omni::decode_timeline_shape(n, w) != hipSuccess) return OMNI_ERR_LAUNCH;
+    *n_workgroups = n;
+    *words_per_workgroup = w;
+    return OMNI_OK;
+}
+
+omni_status omni_debug_decode_timeline(const omni_decode_args* a, uint64_t* stamps, uint64_t n_words, void* hip_stream)
+{
+    if (!a || !stamps) return OMNI_ERR_NULL;
+    int n = 0, w = 0;
+    if (omni::decode_timeline_shape(n, w) != hipSuccess) return OMNI_ERR_LAUNCH;
+    if (n_words < (uint64_t)n * (uint64_t)w) return OMNI_ERR_SHAPE;
+    static_assert(sizeof(unsigned long long) == sizeof(uint64_t), "stamp words are 64 bits");
+    return decode_attn(a, a->workspace, a->workspace_bytes, a->workspace_planned != 0, hip_stream,
+                             reinterpret_cast<unsigned long long*>(stamps));
 }
 
 omni_status omni_debug_ticket_map(uint32_t n_entries, uint32_t n_long_entries, int32_t num_kv_heads,

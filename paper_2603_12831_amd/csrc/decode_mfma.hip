@@ -1185,7 +1185,11 @@ constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming wav
 
 // `fused`: the launch may finish sequences by merging (p.fuse); the plain instance carries none of that code,
 // whose register needs change how the compiler schedules the streaming loop (2 % of the launch).
-template <bool fused, bool half>
+// `timed`: the instance behind omni_debug_decode_timeline, which stamps the constant-rate clock into
+// p.stamps (kStampWords per workgroup) as the workgroup goes along.
+constexpr int kStampWords = 32, kStampTickets = kStampWords - 8;
+
+template <bool fused, bool half, bool timed>
 __device__ __forceinline__ void persistent_body(
     const DecodeParams& p, const int* __restrict__ block_table, unsigned* ticket_counter,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
@@ -1206,6 +1210,11 @@ __device__ __forceinline__ void persistent_body(
     const TicketSpace ts = make_ticket_space(min(counts[0], total), counts[5], (unsigned)p.hkv, gridDim.x);
     const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
+    // [0] start, [1] first Q landed, [2] streaming waves done, [3] writer done, [4] tickets, [5] steps of wave 0,
+    // [8 + k] the workgroup's meeting after ticket k
+    unsigned long long* const stamp = timed ? p.stamps + (size_t)blockIdx.x * kStampWords : nullptr;
+    if (timed && threadIdx.x == 0) stamp[0] = wall_clock64();
+    int n_steps_wave0 = 0;
 
     // rows of empty chunks: LSE = -inf, and the final row of a sequence whose whole range is empty (stores
     // only, shared out over the resident workgroups); and which sequences this call finishes
@@ -1322,6 +1331,10 @@ __device__ __forceinline__ void persistent_body(
                 for (int i = 0; i < n_jobs; ++i) merge_and_store_final(&sh_job[i], id.lane);
             if (last) break;
         }
+        if (timed && id.lane == 0) {
+            OMNI_WAIT_VMCNT(0);
+            stamp[3] = wall_clock64();
+        }
         return;
     }
 
@@ -1347,6 +1360,7 @@ __device__ __forceinline__ void persistent_body(
     read_q<half>(q_buffer(0, it), p.group, id.col, id.kg, qb);
     WaveState st;
     st.reset();
+    if (timed && threadIdx.x == 0) stamp[1] = wall_clock64();
 
     for (int k = 0;; ++k) {
         make_uniform(it);                                  // (the loop-carried copy is where the analysis gives up)
@@ -1435,6 +1449,12 @@ __device__ __forceinline__ void persistent_body(
             si[4 + 4 * id.wave] = it.kvh;
         }
         lds_barrier();
+        if (timed && threadIdx.x == 0) {
+            if (k < kStampTickets) stamp[8 + k] = wall_clock64();
+            if (streamed) n_steps_wave0 += (it.n_steps - it.s0 + it.ds - 1) / it.ds;
+            stamp[4] = (unsigned long long)(k + 1);
+            stamp[5] = (unsigned long long)n_steps_wave0;
+        }
         if (!has_next) break;
         if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by ticket k+4
         read_q<half>(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
@@ -1442,17 +1462,18 @@ __device__ __forceinline__ void persistent_body(
         it = nx;
     }
     OMNI_WAIT_VMCNT(0);                                    // no direct-to-LDS load may outlive the workgroup
+    if (timed && threadIdx.x == 0) stamp[2] = wall_clock64();
     if (gave_up && id.lane == 0) atomicAdd(ticket_counter + 5, 1u);
 }
 
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
-template <bool fused, bool half>
+template <bool fused, bool half, bool timed = false>
 __global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
-    persistent_body<fused, half>(p, block_table, header, counts, entries, arrivals);
+    persistent_body<fused, half, timed>(p, block_table, header, counts, entries, arrivals);
     if (threadIdx.x == 0) {
         const unsigned gone = atomicAdd(header + 3, 1u);   // after this workgroup's last ticket draw
         if (gone == gridDim.x - 1) {
@@ -1541,10 +1562,11 @@ hipError_t device_facts(int& cus)
         f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
         const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
         if (f.status == hipSuccess) {
-            const void* forms[3] = {(const void*)decode_mfma_persistent_kernel<false, false>,
+            const void* forms[4] = {(const void*)decode_mfma_persistent_kernel<false, false>,
                                     (const void*)decode_mfma_persistent_kernel<true, false>,
-                                    (const void*)decode_mfma_persistent_kernel<false, true>};
-            for (int i = 0; i < 3 && f.status == hipSuccess; ++i)
+                                    (const void*)decode_mfma_persistent_kernel<false, true>,
+                                    (const void*)decode_mfma_persistent_kernel<false, false, true>};
+            for (int i = 0; i < 4 && f.status == hipSuccess; ++i)
                 f.status = hipFuncSetAttribute(forms[i], hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
         }
         if (f.status == hipSuccess && lds_g > 64 * 1024) {
@@ -1566,6 +1588,13 @@ hipError_t device_facts(int& cus)
 }
 
 }  // namespace
+
+// Workgroups of a persistent launch on this device (the stamps of a timed launch: kStampWords each)
+hipError_t decode_timeline_shape(int& n_workgroups, int& words_per_workgroup)
+{
+    words_per_workgroup = kStampWords;
+    return device_facts(n_workgroups);
+}
 
 hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool planned, hipStream_t s)
 {
@@ -1601,8 +1630,11 @@ hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool p
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
+    if (p.stamps && (half || p.fuse)) return hipErrorInvalidValue;       // (the API layer does not let this through)
     auto kernel = half ? decode_mfma_persistent_kernel<false, true>
-                       : (p.fuse ? decode_mfma_persistent_kernel<true, false> : decode_mfma_persistent_kernel<false, false>);
+                       : (p.fuse ? decode_mfma_persistent_kernel<true, false>
+                                 : (p.stamps ? decode_mfma_persistent_kernel<false, false, true>
+                                             : decode_mfma_persistent_kernel<false, false>));
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p, p.block_table, header, header + 1,
                        entries, arrivals);
     return hipGetLastError();

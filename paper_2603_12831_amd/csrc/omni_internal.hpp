@@ -32,6 +32,7 @@ struct DecodeParams {
     int out_bf16;
     float* out_lse;                // may be null
     int* seq_final;                // may be null; [batch] 1 = the call wrote the sequence's final row
+    unsigned long long* stamps;    // null, or the time stamps of omni_debug_decode_timeline (device)
     int fuse;                      // 1 = every sequence is finished in the attention launch (persistent form)
     int n_ext;                     // fused form: sources of rows computed elsewhere, folded into the final rows
     omni_partial_src ext[3];
@@ -134,6 +135,7 @@ __device__ __forceinline__ int seq_parts(const DecodeParams& p, int seq, int b, 
 hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s);
 hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s);
+hipError_t decode_timeline_shape(int& n_workgroups, int& words_per_workgroup);
 size_t decode_workspace_bytes(long long batch, long long max_chunks, long long hkv);
 bool decode_mfma_supports(const DecodeParams& p, bool bf16);
 int decode_list_sort_bin(int tokens, int chunk_tokens);

@@ -282,3 +282,31 @@ def test_full_size_fused(name):
     exp = expected_full(w)
     eo, el = check(o, l, exp[0], exp[1], 2e-3, name + " fused")
     print("%s fused: max abs err O %.3g LSE %.3g" % (name, eo, el))
+
+
+def test_timeline_instance_matches_the_plain_kernel():
+    """The time-stamping instance gives the plain call's rows bit for bit, and stamps that are ordered."""
+    w = wl.make_cfg3(batch=40, median=600, lo=1, hi=4000, chunk_tokens=512)
+    o_p, l_p, dw = run_mode(w, "final")
+    n_wg, words = binding.omni_debug_decode_timeline_shape()
+    assert n_wg >= 1 and words >= 16
+    stamps = torch.zeros(n_wg * words, dtype=torch.int64, device="cuda")
+    dw.poison_outputs()
+    args = dw.decode_args(dw.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    binding.omni_debug_decode_timeline(args, stamps)
+    dw.run_merge()
+    o_t, l_t = dw.results()
+    assert np.array_equal(o_t, o_p) and np.array_equal(l_t, l_p)
+    assert dw.abandoned_waves() == 0
+    st = stamps.cpu().numpy().reshape(n_wg, words)
+    busy = st[:, 2] > 0
+    assert busy.any()
+    assert np.all(st[busy, 0] <= st[busy, 1]) and np.all(st[busy, 1] <= st[busy, 2])
+    assert np.all(st[busy, 3] >= st[busy, 1]) and np.all(st[busy, 4] >= 1)
+    n_items = int(live_chunk_count(w).sum()) * w.num_kv_heads
+    assert int(st[busy, 4].sum()) == n_items            # (no short-range grouping in this batch: a ticket is an item)
+    # too small a stamp buffer, and forms without a stamping instance
+    assert binding.omni_debug_decode_timeline(args, stamps[: n_wg * words - 1], check=False) == binding.OMNI_ERR_SHAPE
+    dwg = DeviceWorkload(w, out_dtype="f32", workspace=False, mode="final")
+    argsg = dwg.decode_args(dwg.calls[0], binding.OMNI_KERNEL_AUTO, 0, False)
+    assert binding.omni_debug_decode_timeline(argsg, stamps, check=False) == binding.OMNI_ERR_UNSUPPORTED
