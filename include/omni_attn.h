@@ -355,8 +355,9 @@ omni_status omni_residual_load(const void* store, int64_t n_slots, int32_t row_b
  * sums in fp32, inputs fp32 or bf16.  The call returns when all rows are written; it runs n_threads
  * threads of its own (0 = one per hardware thread) and allocates host scratch of
  * (number of 512-token slices) x G x (head_dim + 2) floats.
- * Errors: NULL, SHAPE (also a row_seq outside [0, batch)), DTYPE, UNSUPPORTED (block_size != 16,
- * head_dim not 64 / 128, G > 16).  n_rows = 0 is OK and does nothing.
+ * Errors: NULL, SHAPE (also a row_seq outside [0, batch), an isa_level outside 0..3), DTYPE, UNSUPPORTED
+ * (block_size != 16, head_dim not 64 / 128, G > 16, an isa_level the CPU lacks).  n_rows = 0 is OK and
+ * does nothing.
  */
 typedef struct {
     int32_t n_rows;
@@ -374,6 +375,10 @@ typedef struct {
     float* part_o;                 /* [n_rows, num_q_heads, head_dim]                        */
     float* part_lse;               /* [n_rows, num_q_heads]                                  */
     int32_t n_threads;
+    /* instruction-set level of the inner loops: 0 = the best this CPU reports; 1 = plain x86-64,
+     * 2 = AVX2 + FMA, 3 = AVX-512 (F, VL, BW, DQ) - UNSUPPORTED if the CPU lacks the level asked
+     * for.  Levels differ in rounding order only (all within the tolerances of the path).      */
+    int32_t isa_level;
 } omni_host_attn_args;
 
 omni_status omni_host_partial_attn(const omni_host_attn_args* a);

@@ -81,7 +81,7 @@ class omni_host_attn_args(ctypes.Structure):
                 ("q", ctypes.c_void_p), ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p),
                 ("block_table", ctypes.c_void_p), ("row_seq", ctypes.c_void_p), ("row_begin", ctypes.c_void_p),
                 ("row_end", ctypes.c_void_p), ("part_o", ctypes.c_void_p), ("part_lse", ctypes.c_void_p),
-                ("n_threads", ctypes.c_int32)]
+                ("n_threads", ctypes.c_int32), ("isa_level", ctypes.c_int32)]
 
 
 _lib = None
@@ -542,10 +542,11 @@ def omni_residual_load(store, slot_ids, rows_out, stream=None, check: bool = Tru
 
 
 def omni_host_partial_attn(q, k_pool, v_pool, block_table, row_seq, row_begin, row_end, sm_scale: float,
-                           dtype: str, n_threads: int = 0, check: bool = True):
+                           dtype: str, n_threads: int = 0, check: bool = True, isa_level: int = 0):
     """Partial rows computed on the host's cores from KV in host memory.  q, k_pool, v_pool: C-contiguous
     numpy arrays (float32, or uint16 holding bf16 bit patterns when dtype == "bf16") in the layouts of the
     decode call; block_table int32 [batch, max_blocks]; row_seq / row_begin / row_end int32 [n_rows].
+    isa_level: 0 best available, 1 plain, 2 AVX2 + FMA, 3 AVX-512.
     Returns (part_o [n_rows, Hq, D] float32, part_lse [n_rows, Hq] float32)."""
     import numpy as np
     want = np.uint16 if dtype == "bf16" else np.float32
@@ -568,7 +569,7 @@ def omni_host_partial_attn(q, k_pool, v_pool, block_table, row_seq, row_begin, r
         q=q.ctypes.data, k_pool=k_pool.ctypes.data, v_pool=v_pool.ctypes.data,
         block_table=block_table.ctypes.data, row_seq=row_seq.ctypes.data,
         row_begin=None if row_begin is None else row_begin.ctypes.data, row_end=row_end.ctypes.data,
-        part_o=part_o.ctypes.data, part_lse=part_lse.ctypes.data, n_threads=int(n_threads))
+        part_o=part_o.ctypes.data, part_lse=part_lse.ctypes.data, n_threads=int(n_threads), isa_level=int(isa_level))
     st = load_library().omni_host_partial_attn(ctypes.byref(a))
     if check and st != OMNI_OK:
         raise OmniError(st, "omni_host_partial_attn")

@@ -48,9 +48,9 @@ inline float bf16_to_f32(uint16_t h)
     return f;
 }
 
-// The compute of a unit is instantiated for three instruction-set levels (baseline x86-64, AVX2 + FMA,
-// AVX-512) and the level is chosen once per call from what the CPU reports; the bodies below are plain
-// loops over whole rows that the compiler vectorises for each level.
+// The compute of a unit exists for three instruction-set levels (plain x86-64, AVX2 + FMA, AVX-512) and the
+// level is chosen once per call from what the CPU reports (or by the caller).  The first two are the plain
+// loops below, which the compiler vectorises for each level; the AVX-512 level is written out further down.
 #define OMNI_HOST_INLINE static inline __attribute__((always_inline))
 
 // e^x for x <= 0 (a weight exp(s - max)) from plain arithmetic, so that a loop over the tokens of a page
@@ -328,21 +328,22 @@ OMNI_AVX512_TARGET static void unit_avx512_128(const HostParams& p, const Unit& 
     run_unit_avx512<128>(p, u, m, l, acc);
 }
 
-UnitFn pick_unit_fn(int d)
+// level: 0 = best available, 1 = plain, 2 = AVX2 + FMA, 3 = AVX-512; null if the CPU lacks the level
+UnitFn pick_unit_fn(int d, int level)
 {
     __builtin_cpu_init();
-    if (__builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512vl") &&
-        __builtin_cpu_supports("avx512bw") && __builtin_cpu_supports("avx512dq"))
-        return d == 128 ? unit_avx512_128 : unit_avx512_64;
-    if (__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma"))
-        return d == 128 ? unit_avx2_128 : unit_avx2_64;
+    const bool avx512 = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512vl") &&
+                        __builtin_cpu_supports("avx512bw") && __builtin_cpu_supports("avx512dq");
+    const bool avx2 = __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma");
+    if (level == 0) level = avx512 ? 3 : (avx2 ? 2 : 1);
+    if (level == 3) return avx512 ? (d == 128 ? unit_avx512_128 : unit_avx512_64) : nullptr;
+    if (level == 2) return avx2 ? (d == 128 ? unit_avx2_128 : unit_avx2_64) : nullptr;
     return d == 128 ? unit_base_128 : unit_base_64;
 }
 
 template <int D>
-void produce(const HostParams& p, int n_threads)
+void produce(const HostParams& p, int n_threads, UnitFn unit_fn)
 {
-    const UnitFn unit_fn = pick_unit_fn(D);
     // units, grouped by (row, kv head) in order
     std::vector<Unit> units;
     std::vector<size_t> first_unit((size_t)p.n_rows * p.hkv + 1, 0);
@@ -418,7 +419,7 @@ void produce(const HostParams& p, int n_threads)
 extern "C" omni_status omni_host_partial_attn(const omni_host_attn_args* a)
 {
     if (!a) return OMNI_ERR_NULL;
-    if (a->n_rows < 0 || a->batch < 0) return OMNI_ERR_SHAPE;
+    if (a->n_rows < 0 || a->batch < 0 || a->isa_level < 0 || a->isa_level > 3) return OMNI_ERR_SHAPE;
     if (a->n_rows == 0) return OMNI_OK;
     if (!a->q || !a->k_pool || !a->v_pool || !a->block_table || !a->row_seq || !a->row_end || !a->part_o ||
         !a->part_lse)
@@ -455,8 +456,10 @@ extern "C" omni_status omni_host_partial_attn(const omni_host_attn_args* a)
     p.part_lse = a->part_lse;
     int n_threads = a->n_threads;
     if (n_threads <= 0) n_threads = (int)std::max(1u, std::thread::hardware_concurrency());
-    if (p.d == 128) produce<128>(p, n_threads);
-    else produce<64>(p, n_threads);
+    const UnitFn unit_fn = pick_unit_fn(p.d, a->isa_level);
+    if (!unit_fn) return OMNI_ERR_UNSUPPORTED;
+    if (p.d == 128) produce<128>(p, n_threads, unit_fn);
+    else produce<64>(p, n_threads, unit_fn);
     return OMNI_OK;
 }
 

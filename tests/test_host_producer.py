@@ -42,7 +42,8 @@ def check_rows(got_o, got_l, exp_o, exp_l, tol):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(8, 2, 64), (8, 8, 128), (32, 8, 128), (16, 1, 128), (6, 3, 64)])
+@pytest.mark.parametrize("shape", [(8, 2, 64), (8, 8, 128), (32, 8, 128), (16, 1, 128), (6, 3, 64), (12, 4, 128), (10, 2, 64),
+                                   (14, 2, 128), (12, 1, 64)])
 def test_rows_match_oracle(shape, dtype):
     """Ragged rows: unaligned begins and ends, empty rows, ranges longer than a 512-token slice (so that
     slices are folded), several rows per sequence."""
@@ -57,6 +58,26 @@ def test_rows_match_oracle(shape, dtype):
                                                   w.sm_scale, dtype, n_threads=8)
     exp_o, exp_l = oracle_rows(w, seq, begin, end)
     check_rows(got_o, got_l, exp_o, exp_l, TOL[dtype])
+
+
+@pytest.mark.parametrize("level", [1, 2, 3])
+@pytest.mark.parametrize("dtype,shape", [("bf16", (8, 2, 128)), ("f32", (6, 1, 64)), ("bf16", (10, 2, 64)), ("f32", (12, 4, 128))])
+def test_every_instruction_set_level(level, dtype, shape):
+    """The plain, AVX2 and AVX-512 forms of the inner loops each against the oracle (a level the CPU lacks
+    is refused, not emulated), and each independent of the thread count."""
+    hq, hkv, d = shape
+    rng = np.random.default_rng([75, hq, hkv, d])
+    w = wl.make_generic(75 + hq, rng.integers(1, 1200, size=5), hq, hkv, d, dtype=dtype, pool_factor=1.5)
+    seq, begin, end = rows_for(w, rng, 14, 1100)
+    args = (w.q, w.k_pool, w.v_pool, w.block_table, seq, begin, end, w.sm_scale, dtype)
+    st = binding.omni_host_partial_attn(*args, n_threads=4, check=False, isa_level=level)
+    if st == binding.OMNI_ERR_UNSUPPORTED:
+        pytest.skip("this CPU lacks instruction-set level %d" % level)
+    got_o, got_l = binding.omni_host_partial_attn(*args, n_threads=4, isa_level=level)
+    exp_o, exp_l = oracle_rows(w, seq, begin, end)
+    check_rows(got_o, got_l, exp_o, exp_l, TOL[dtype])
+    one_o, one_l = binding.omni_host_partial_attn(*args, n_threads=1, isa_level=level)
+    assert np.array_equal(one_o, got_o) and np.array_equal(one_l, got_l)
 
 
 def test_result_does_not_depend_on_thread_count():
