@@ -296,7 +296,10 @@ omni_status omni_kv_scatter_pages(const omni_kv_cache* c, const int32_t* page_id
  * A queue is a ring of `capacity` rows of `row_bytes` bytes (a multiple of 16), an optional int32 tag per
  * row (e.g. the request id) and four uint32 state words {head, tail, 0, 0} that the caller zeroes once:
  * head / tail count rows popped / pushed since then, a row with count c lives in slot c % capacity.
- * Calls on one queue must be ordered (same stream).
+ * The ring is at most 2 GiB - 1 bytes (capacity * row_bytes; UNSUPPORTED beyond).
+ * Calls on one queue must be ordered (same stream).  Inside a call the rows are written (through the
+ * caches, at device scope) before the pointer that announces them; what a later call on the stream sees
+ * is ordered by the stream.
  */
 typedef struct {
     void*     data;                /* [capacity, row_bytes]                                      */
@@ -308,7 +311,7 @@ typedef struct {
 /*
  * Push n_rows rows (rows [n_rows, row_bytes], tags [n_rows] or NULL) at the tail — all of them, or, if
  * they do not all fit, none; *n_pushed (device int32, may be NULL) receives n_rows or 0.
- * Errors: NULL, SHAPE (capacity, row_bytes, n_rows), LAUNCH.
+ * Errors: NULL, SHAPE (capacity, row_bytes, n_rows), UNSUPPORTED (ring of 2 GiB or more), LAUNCH.
  */
 omni_status omni_queue_push(const omni_queue* q, const void* rows, const int32_t* tags, int32_t n_rows,
                             int32_t* n_pushed, void* hip_stream);

@@ -288,6 +288,7 @@ static omni_status flatten_queue(const omni_queue* q, QueueParams& k, int32_t n_
 {
     if (!q) return OMNI_ERR_NULL;
     if (q->capacity <= 0 || q->row_bytes <= 0 || q->row_bytes % 16 != 0 || n_rows < 0) return OMNI_ERR_SHAPE;
+    if ((long long)q->capacity * q->row_bytes > 0x7fffffffLL) return OMNI_ERR_UNSUPPORTED;       // 32-bit offsets in the ring
     if (!q->data || !q->state) return OMNI_ERR_NULL;
     k.data = q->data; k.tags = q->tags; k.state = q->state; k.capacity = q->capacity; k.row_bytes = q->row_bytes;
     return OMNI_OK;
