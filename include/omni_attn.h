@@ -421,8 +421,8 @@ omni_status omni_debug_host_stream_read(const void* src, size_t bytes, int32_t n
  * [8 + k] the workgroup's meeting after its k-th ticket (the first words_per_workgroup - 8 tickets).  A
  * workgroup without work stamps [0] only.  omni_debug_decode_timeline_shape tells how many workgroups a
  * launch on the current device has and how many words each writes.  Outputs are those of the plain call.
- * Errors: as omni_paged_decode_attn; UNSUPPORTED unless the call runs the plain persistent form at head_dim
- * 128 (workspace given, fuse_merge 0); SHAPE if n_words is too small.
+ * Errors: as omni_paged_decode_attn; UNSUPPORTED unless the call runs the persistent form at head_dim 128
+ * (workspace given); SHAPE if n_words is too small.
  */
 omni_status omni_debug_decode_timeline_shape(int32_t* n_workgroups, int32_t* words_per_workgroup);
 omni_status omni_debug_decode_timeline(const omni_decode_args* a, uint64_t* stamps, uint64_t n_words, void* hip_stream);

@@ -52,6 +52,8 @@ omni_status flatten(const omni_decode_args* a, DecodeParams& p, bool need_output
         if (misaligned(a->q) || misaligned(a->k_pool) || misaligned(a->v_pool) || misaligned(a->part_o) ||
             misaligned(a->out_o))
             return OMNI_ERR_SHAPE;
+        for (int i = 0; i < a->n_ext_srcs; ++i)
+            if (misaligned(a->ext_srcs[i].o)) return OMNI_ERR_SHAPE;
     }
     p.batch = a->batch; p.hq = a->num_q_heads; p.hkv = a->num_kv_heads; p.d = a->head_dim;
     p.max_blocks = a->max_blocks_per_seq; p.group = a->num_q_heads / a->num_kv_heads;
@@ -99,8 +101,8 @@ omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_b
     }
     // only the persistent form finishes every sequence, and only at head_dim 128
     if (p.fuse && (!ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
-    // the time-stamping instance is one of the plain persistent form at head_dim 128
-    if (p.stamps && (!mfma || !ws || p.d != 128 || p.fuse)) return OMNI_ERR_UNSUPPORTED;
+    // the time-stamping instances are of the persistent form at head_dim 128
+    if (p.stamps && (!mfma || !ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
     hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }

@@ -315,10 +315,12 @@ struct LaneIds {
 // Vector-memory operations retire in order, and every request for a step is "8 K loads, then 8 V
 // loads": once at most 8 operations are outstanding the K tiles have landed, whatever was issued
 // after them.
-template <bool more, bool half>
+// `before_v` runs right before the V request that ends the step: requests made there are older than that V
+// and younger than everything this step still waits for, so they delay nothing in it.
+template <bool more, bool half, class BeforeV>
 __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                             const u32x4 (&qb)[4], const LaneIds& id, int s, bool ok_a, bool ok_b,
-                                            Pages next, int next_kvh, float scale2)
+                                            Pages next, int next_kvh, float scale2, BeforeV&& before_v)
 {
     const int kg = id.kg;
     // ---- S^T = K . Q^T for both pages ----------------------------------------------------------
@@ -433,6 +435,7 @@ __device__ __forceinline__ void attend_step(const DecodeParams& p, const Item& i
         st.acc[2 * jj + 1] = a1;
     }
     __builtin_amdgcn_sched_barrier(0);
+    before_v();
     if (more) issue_v(p, next_kvh, next, id.v_lane_off, r);
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -450,10 +453,10 @@ struct Tail {
 // after the wave's second-to-last step (if it has two or more).  The wave's last step is peeled off:
 // `before_last` runs right before it and returns what the wave requests during it instead of a further
 // step of this item, `after_last` runs right after it.
-template <bool chained, bool half, class Penult, class Before, class After>
+template <bool chained, bool half, class Penult, class Before, class Mid, class After>
 __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, WaveState& st, StepRegs& r,
                                          const u32x4 (&qb)[4], const LaneIds& id, float scale2, Pages cur, Pages nxt,
-                                         Penult&& at_penult, Before&& before_last, After&& after_last)
+                                         Penult&& at_penult, Before&& before_last, Mid&& in_last, After&& after_last)
 {
     int s = it.s0;
     // everything older than the first step's 8 K + 8 V requests has landed
@@ -463,7 +466,7 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
         Pages nn = {-1, -1};
         if (!penult) nn = step_pages<half>(p, it, s + 2 * it.ds);                        // table reads run a step ahead
         else at_penult(true);
-        attend_step<true, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2);
+        attend_step<true, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, nxt, it.kvh, scale2, [] {});
         if (penult) at_penult(false);
         cur = nxt;
         nxt = nn;
@@ -475,8 +478,8 @@ __device__ __forceinline__ void run_item(const DecodeParams& p, const Item& it, 
         // none, the same loads on two absent pages, which fetch nothing), so that one copy of the step code with exact load
         // counts serves; a second copy for "nothing follows" cost registers to the point of spilling
         if (chained) attend_step<true, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0,
-                                       tail.valid ? tail.pages : Pages{-1, -1}, tail.valid ? tail.kvh : 0, scale2);
-        else attend_step<false, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.pages, tail.kvh, scale2);
+                                       tail.valid ? tail.pages : Pages{-1, -1}, tail.valid ? tail.kvh : 0, scale2, in_last);
+        else attend_step<false, half>(p, it, st, r, qb, id, s, cur.a >= 0, cur.b >= 0, tail.pages, tail.kvh, scale2, in_last);
         after_last();
     }
 }
@@ -869,6 +872,97 @@ __device__ __forceinline__ void merge_job(MergeJob& j, const DecodeParams& p, in
     }
 }
 
+// Rows computed elsewhere for an item that finishes its sequence, brought into LDS while the item streams:
+// up to kExtLdsRows rows of the item's G heads (G <= kExtLdsGroup) from the call's single external source.
+// A slot holds [row][G][128] floats of O and behind them [row][G] LSE values.  The loads are direct-to-LDS
+// ones issued by the wave that also requests the item's Q rows, right after those: they need no registers,
+// are older than the item's first K / V requests and have landed with Q.  Always kExtLdsRows row requests:
+// rows beyond `n` lie outside the buffer resource and fetch nothing (fixed instruction count).
+constexpr int kExtLdsRows = 4, kExtLdsGroup = 4;
+__host__ __device__ __forceinline__ size_t ext_slot_bytes(int group)
+{
+    return (size_t)kExtLdsRows * group * kD * 4 + 64;
+}
+__device__ __forceinline__ void issue_ext(const DecodeParams& p, const Item& it, int r0, int n, int lane, char* slot)
+{
+    const int G = p.group, row_lds = G * kD * 4, row_bytes = p.hq * kD * 4;
+    const float* o0 = p.ext[0].o + ((long long)r0 * p.hq + (long long)it.kvh * G) * kD;
+    const __amdgpu_buffer_rsrc_t rs = byte_buffer(o0, (n - 1) * row_bytes + row_lds);
+#pragma unroll
+    for (int e = 0; e < kExtLdsRows; ++e)
+        for (int i = 0; i * 1024 < row_lds; ++i)
+            if (lane * 16 + i * 1024 < row_lds)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(slot + e * row_lds + i * 1024), 16,
+                                                         lane * 16 + i * 1024 + e * row_bytes, 0, 0, 0);
+    const float* l0 = p.ext[0].lse + (long long)r0 * p.hq + (long long)it.kvh * G;
+    const __amdgpu_buffer_rsrc_t rl = byte_buffer(l0, ((n - 1) * p.hq + G) * 4);
+    if (lane < kExtLdsRows * G) {                          // lane = row * G + head
+        const int e = lane / G, g = lane - e * G;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rl, (lds_void*)(slot + kExtLdsRows * row_lds), 4, (e * p.hq + g) * 4, 0, 0, 0);
+    }
+}
+
+// after a barrier: the final rows of an item whose sequence ends here, from the states of waves w0 .. w1-1
+// and the n rows waiting in the item's LDS slot (own state first, then the rows in order)
+template <int n>
+__device__ __forceinline__ void combine_fold_store(const DecodeParams& p, const Item& it, const float* area,
+                                                   int lane, int w0, int w1, const char* slot)
+{
+    const int G = p.group;
+    const long long orow0 = (long long)it.seq * p.hq + (long long)it.kvh * G;
+    const float* e_o = reinterpret_cast<const float*>(slot);
+    const float* e_lse = reinterpret_cast<const float*>(slot + (size_t)kExtLdsRows * G * kD * 4);
+    // Two (head, four dims) positions per lane and turn, and every LDS read of a turn before anything is used:
+    // this wave works alone and in order, so what its work costs is its chains of waits.
+    constexpr int kSide = 2;
+    for (int base = lane; base < G * (kD / 4); base += kSide * kWave) {
+        int g[kSide], d[kSide];
+        bool on[kSide];
+        float le[kSide][n], lse[kSide];
+        f32x4 x[kSide][n], o[kSide];
+#pragma unroll
+        for (int k = 0; k < kSide; ++k) {
+            const int idx = base + k * kWave;
+            on[k] = idx < G * (kD / 4);
+            g[k] = on[k] ? idx >> 5 : 0;
+            d[k] = (idx & 31) * 4;
+#pragma unroll
+            for (int e = 0; e < n; ++e) {
+                le[k][e] = on[k] ? e_lse[e * G + g[k]] : -INFINITY;
+                x[k][e] = *reinterpret_cast<const f32x4*>(e_o + (size_t)(e * G + g[k]) * kD + d[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSide; ++k) combine_quad<false>(area, G, on[k] ? base + k * kWave : 0, w0, w1, o[k], lse[k]);
+#pragma unroll
+        for (int k = 0; k < kSide; ++k) {
+            float m = lse[k];
+#pragma unroll
+            for (int e = 0; e < n; ++e) m = fmaxf(m, le[k][e]);
+            f32x4 out = {0.f, 0.f, 0.f, 0.f};
+            float out_lse = -INFINITY;
+            if (m != -INFINITY) {
+                // own state first, then the rows in order; a row without weight may hold anything and is left out
+                float wsum = lse[k] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((lse[k] - m) * kLog2e);
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] = lse[k] == -INFINITY ? 0.f : wsum * o[k][c];
+#pragma unroll
+                for (int e = 0; e < n; ++e) {
+                    const bool live = le[k][e] != -INFINITY;
+                    const float w = live ? __builtin_amdgcn_exp2f((le[k][e] - m) * kLog2e) : 0.f;
+                    wsum += w;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[c] += live ? w * x[k][e][c] : 0.f;
+                }
+                out = acc * (1.f / wsum);
+                out_lse = m + __builtin_amdgcn_logf(wsum) * kLn2;
+            }
+            if (on[k]) store_final_quad(p.out_o, p.out_lse, p.out_bf16 != 0, orow0 + g[k], d[k], out, out_lse);
+        }
+    }
+}
+
 // after a barrier: the item's rows from the states of waves w0 .. w1-1, and their stores (only seq, chunk and
 // kvh of `it` are used); thread `tid` of `nthreads` takes four dims of one head per turn.  The fold of rows
 // from other sources is the out-of-line merge's (one wave calls this then).
@@ -971,7 +1065,8 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
         issue_step(p, it.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
     }
     if (id.wave + kWaves < it.n_steps) second = step_pages<half>(p, it, id.wave + kWaves);
-    run_item<false, half>(p, it, st, r, qb, id, scale2, cur, second, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; }, [] {});
+    run_item<false, half>(p, it, st, r, qb, id, scale2, cur, second, [](bool) {}, [] { return Tail{false, 0, Pages{-1, -1}}; },
+                          [] {}, [] {});
     __syncthreads();
     stage_wave_state(st, lds, half ? 4 * p.group : p.group, id.wave, id.col, id.kg);
     __syncthreads();
@@ -1181,7 +1276,9 @@ __device__ __forceinline__ Item ticket_item(const DecodeParams& p, const WorkEnt
     return it;
 }
 
-constexpr int kItemWords = 2 + 4 * kWaves;             // what the streaming waves tell the writer about an item
+// what the streaming waves tell the writer about an item: [0] last ticket, [1] grouped, then per wave (seq,
+// chunk word, kv head, rows from elsewhere as bring_ext returns them)
+constexpr int kItemWords = 2 + 4 * kWaves;
 
 // `fused`: the launch may finish sequences by merging (p.fuse); the plain instance carries none of that code,
 // whose register needs change how the compiler schedules the streaming loop (2 % of the launch).
@@ -1205,6 +1302,12 @@ __device__ __forceinline__ void persistent_body(
     char* const stage_base = reinterpret_cast<char*>(lds) + 2 * comb_bytes;
     char* const q_base = stage_base + kWaves * kStageBytes;          // [parity][wave] buffers of G rows
     const int q_bytes = p.group * kD * 2;
+    // fused form with one external source and few heads: [ticket % 3][wave] slots for the rows of items that
+    // finish their sequence (see issue_ext).  Three deep: while the rows for ticket k+2 arrive (requested in
+    // the last step of ticket k+1), the writer wave may still be reading those of ticket k.
+    const bool ext_lds = fused && p.n_ext == 1 && p.group <= kExtLdsGroup;
+    char* const ext_base = q_base + 2 * kWaves * q_bytes;
+    const size_t ext_bytes = ext_slot_bytes(p.group);
     const LaneIds id(stage_base);
     const unsigned total = (unsigned)(p.batch * p.max_chunks);
     const TicketSpace ts = make_ticket_space(min(counts[0], total), counts[5], (unsigned)p.hkv, gridDim.x);
@@ -1261,6 +1364,32 @@ __device__ __forceinline__ void persistent_body(
     auto q_buffer = [&](int parity, const Item& x) {
         return q_base + (parity * kWaves + (x.ds == 1 ? id.wave : 0)) * q_bytes;
     };
+    // What an item's final row still needs from the call's external sources, for the wave that brings its Q
+    // rows: `rows` = 0: nothing (not the sequence's only part, or no rows there), n > 0: n rows from row `first`
+    // on that go through the item's LDS slot, -1: rows that do not (the merge routine fetches them).
+    struct ExtRows { int rows, first; };
+    auto ext_slot = [&](int third, int wave) { return ext_base + (size_t)(third * kWaves + wave) * ext_bytes; };
+    auto ext_rows = [&](const Item& x) {                   // (scalar loads: call it where the item's pages are read)
+        if (!fused || row_mode(p, chunk_live(x.chunk)) != kRowFinalFold) return ExtRows{0, 0};
+        int n_all = 0, r0 = 0, r1 = 0;
+        for (int s = 0; s < p.n_ext; ++s) {
+            if (p.ext[s].row_offsets) {
+                r0 = load_invariant(p.ext[s].row_offsets + x.seq);
+                r1 = load_invariant(p.ext[s].row_offsets + x.seq + 1);
+            } else {
+                r0 = x.seq * p.ext[s].dense_rows_per_seq;
+                r1 = r0 + p.ext[s].dense_rows_per_seq;
+            }
+            n_all += max(r1 - r0, 0);
+        }
+        n_all = uniform(n_all);
+        if (n_all == 0) return ExtRows{0, 0};
+        if (!ext_lds || n_all > kExtLdsRows) return ExtRows{-1, 0};
+        return ExtRows{n_all, uniform(r0)};
+    };
+    auto bring_ext = [&](int third, const Item& x, ExtRows e) {
+        if (fused && e.rows > 0) issue_ext(p, x, e.first, e.rows, id.lane, ext_slot(third, x.ds == 1 ? id.wave : 0));
+    };
     unsigned tk = blockIdx.x;
     const bool writer = id.wave == kWaves;                 // the fifth wave
     if (writer) store_empty_share();
@@ -1296,8 +1425,23 @@ __device__ __forceinline__ void persistent_body(
                 done.chunk = uniform(si[3 + 4 * w]);
                 done.kvh = uniform(si[4 + 4 * w]);
                 if (done.seq < 0) continue;
-                const int mode = row_mode(p, chunk_live(done.chunk));
+                int mode = row_mode(p, chunk_live(done.chunk));
                 shared |= mode == kRowShared;
+                if (fused && mode == kRowFinalFold) {
+                    // rows from elsewhere: none (a plain final row), waiting in the item's LDS slot, or the merge routine's
+                    const int ext = uniform(si[5 + 4 * w]);
+                    if (ext == 0) mode = kRowFinal;
+                    if (ext > 0) {
+                        const int w0 = grouped ? w : 0, w1 = grouped ? w + 1 : kWaves;
+                        const char* slot = ext_slot(k % 3, w);
+                        // (the row count as a constant: the rows' loads and weights are straight-line code)
+                        if (ext == 1) combine_fold_store<1>(p, done, area, id.lane, w0, w1, slot);
+                        else if (ext == 2) combine_fold_store<2>(p, done, area, id.lane, w0, w1, slot);
+                        else if (ext == 3) combine_fold_store<3>(p, done, area, id.lane, w0, w1, slot);
+                        else combine_fold_store<4>(p, done, area, id.lane, w0, w1, slot);
+                        continue;
+                    }
+                }
                 MergeJob* job = &sh_job[n_jobs];
                 if (grouped) combine_and_store<fused, half>(p, done, area, p.group, id.lane, kWave, mode, job, w, w + 1);
                 else combine_and_store<fused, half>(p, done, area, p.group, id.lane, kWave, mode, job);
@@ -1346,7 +1490,13 @@ __device__ __forceinline__ void persistent_body(
         sh_ticket[2] = kPending;
         sh_ticket[1] = short_item(it) ? first_dynamic + atomicAdd(ticket_counter, 1u) : kPending;
     }
-    if (brings_q(it)) issue_q(p, it, id.lane, q_buffer(0, it));
+    int it_ext = 0;                                        // ext_rows(...).rows of the current item (in the wave that brings its Q)
+    if (brings_q(it)) {
+        issue_q(p, it, id.lane, q_buffer(0, it));
+        const ExtRows e = ext_rows(it);
+        bring_ext(0, it, e);
+        it_ext = e.rows;
+    }
     StepRegs r;
     Pages cur = {-1, -1}, second = {-1, -1};              // pages of the wave's first and second step of the item
     if (has_steps(it)) {
@@ -1372,6 +1522,7 @@ __device__ __forceinline__ void persistent_body(
         Tail tail = {false, 0, Pages{-1, -1}};
         Pages next_second = {-1, -1};
         bool has_next = false, q_coming = false;
+        ExtRows nx_ext = {0, 0};
         unsigned t1 = 0, t2 = 0;
         bool draw2 = false;
 
@@ -1395,6 +1546,7 @@ __device__ __forceinline__ void persistent_body(
                 next_second = Pages{-1, -1};
                 if (nx.s0 + nx.ds < nx.n_steps) next_second = step_pages<half>(p, nx, nx.s0 + nx.ds);
                 q_coming = brings_q(nx);
+                if (fused && q_coming) nx_ext = ext_rows(nx);
             } else {
                 nx.n_steps = 0;
             }
@@ -1416,13 +1568,17 @@ __device__ __forceinline__ void persistent_body(
                      if (threadIdx.x == 0 && draw2) t2 = atomicAdd(ticket_counter, 1u);
                      return tail;
                  },
+                 [&] { bring_ext((k + 1) % 3, nx, nx_ext); },
                  [&] {
                      if (threadIdx.x == 0 && draw2) lds_post(&sh_ticket[(k + 2) % 3], first_dynamic + t2);
                  });
         // waves that had no step under this ticket request their Q and first step of the next one now
         if (!streamed) {
             acquire();
-            if (q_coming) issue_q(p, nx, id.lane, q_buffer(parity_next, nx));
+            if (q_coming) {
+                issue_q(p, nx, id.lane, q_buffer(parity_next, nx));
+                bring_ext((k + 1) % 3, nx, nx_ext);
+            }
         }
 
         // accumulators go to LDS (the ticket's combine area); whoever requested Q rows makes sure they have
@@ -1436,7 +1592,14 @@ __device__ __forceinline__ void persistent_body(
         if (tail.valid && !streamed) {
             issue_step(p, nx.kvh, cur, id.lane, id.stage, id.v_lane_off, r);
         }
-        if (q_coming) OMNI_WAIT_VMCNT(16);
+        if (q_coming) {
+            // Q is older than the 16 K / V requests behind it - and than the requests for rows from elsewhere,
+            // when those went out between that K and that V (4 rows of one or two KiB, and the LSE values)
+            const int between = (fused && streamed && nx_ext.rows > 0) ? kExtLdsRows * ((p.group * kD * 4 + 1023) / 1024) + 1 : 0;
+            if (between == 9) OMNI_WAIT_VMCNT(25);
+            else if (between == 5) OMNI_WAIT_VMCNT(21);
+            else OMNI_WAIT_VMCNT(16);
+        }
         const bool grouped = it.ds == 1;
         if (id.lane == 0 && (grouped || id.wave == 0)) {
             int* si = sh_item[k & 1];
@@ -1447,6 +1610,7 @@ __device__ __forceinline__ void persistent_body(
             si[2 + 4 * id.wave] = streamed ? it.seq : -1;
             si[3 + 4 * id.wave] = it.chunk;
             si[4 + 4 * id.wave] = it.kvh;
+            if (fused) si[5 + 4 * id.wave] = it_ext;
         }
         lds_barrier();
         if (timed && threadIdx.x == 0) {
@@ -1460,6 +1624,7 @@ __device__ __forceinline__ void persistent_body(
         read_q<half>(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
         st.reset();
         it = nx;
+        it_ext = nx_ext.rows;
     }
     OMNI_WAIT_VMCNT(0);                                    // no direct-to-LDS load may outlive the workgroup
     if (timed && threadIdx.x == 0) stamp[2] = wall_clock64();
@@ -1483,13 +1648,14 @@ __global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_
     }
 }
 
-size_t lds_bytes(int group, bool persistent)
+size_t lds_bytes(int group, bool persistent, bool fused = false)
 {
     if (!persistent) {
         const size_t a = combine_bytes(group), b = (size_t)kWaves * kStageBytes;
         return a > b ? a : b;
     }
-    return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)kWaves * group * kD * 2;
+    const size_t ext = (fused && group <= kExtLdsGroup) ? 3 * (size_t)kWaves * ext_slot_bytes(group) : 0;
+    return 2 * combine_bytes(group) + (size_t)kWaves * kStageBytes + 2 * (size_t)kWaves * group * kD * 2 + ext;
 }
 
 }  // namespace
@@ -1560,13 +1726,15 @@ hipError_t device_facts(int& cus)
     DeviceFacts& f = facts[dev];
     if (!f.known) {
         f.status = hipDeviceGetAttribute(&f.cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const int lds_p = (int)lds_bytes(16, true), lds_g = (int)lds_bytes(16, false);
+        const int lds_p = (int)std::max(lds_bytes(16, true), lds_bytes(kExtLdsGroup, true, true));
+        const int lds_g = (int)lds_bytes(16, false);
         if (f.status == hipSuccess) {
-            const void* forms[4] = {(const void*)decode_mfma_persistent_kernel<false, false>,
+            const void* forms[5] = {(const void*)decode_mfma_persistent_kernel<false, false>,
                                     (const void*)decode_mfma_persistent_kernel<true, false>,
                                     (const void*)decode_mfma_persistent_kernel<false, true>,
-                                    (const void*)decode_mfma_persistent_kernel<false, false, true>};
-            for (int i = 0; i < 4 && f.status == hipSuccess; ++i)
+                                    (const void*)decode_mfma_persistent_kernel<false, false, true>,
+                                    (const void*)decode_mfma_persistent_kernel<true, false, true>};
+            for (int i = 0; i < 5 && f.status == hipSuccess; ++i)
                 f.status = hipFuncSetAttribute(forms[i], hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
         }
         if (f.status == hipSuccess && lds_g > 64 * 1024) {
@@ -1607,7 +1775,7 @@ hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool p
         p.hkv = given.hkv / 2;
         if (p.fuse) return hipErrorInvalidValue;           // (the API layer does not let this through)
     }
-    const size_t lds = lds_bytes(half ? 4 * p.group : p.group, workspace != nullptr);
+    const size_t lds = lds_bytes(half ? 4 * p.group : p.group, workspace != nullptr, p.fuse != 0);
     int cus = 0;
     hipError_t e = device_facts(cus);
     if (e != hipSuccess) return e;
@@ -1630,9 +1798,9 @@ hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool p
     long long want = (long long)cus, cap = (long long)p.batch * p.max_chunks * p.hkv;
     const unsigned grid = (unsigned)(want < cap ? want : cap);
     unsigned* arrivals = reinterpret_cast<unsigned*>(entries + (size_t)p.batch * p.max_chunks);
-    if (p.stamps && (half || p.fuse)) return hipErrorInvalidValue;       // (the API layer does not let this through)
+    if (p.stamps && half) return hipErrorInvalidValue;                   // (the API layer does not let this through)
     auto kernel = half ? decode_mfma_persistent_kernel<false, true>
-                       : (p.fuse ? decode_mfma_persistent_kernel<true, false>
+                       : (p.fuse ? (p.stamps ? decode_mfma_persistent_kernel<true, false, true> : decode_mfma_persistent_kernel<true, false>)
                                  : (p.stamps ? decode_mfma_persistent_kernel<false, false, true>
                                              : decode_mfma_persistent_kernel<false, false>));
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p, p.block_table, header, header + 1,

@@ -19,6 +19,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--launches", type=int, default=20)
+    ap.add_argument("--fused", action="store_true", help="the fused form (the launch finishes every sequence)")
     args = ap.parse_args()
     import torch
     from paper_2603_12831_amd import binding, workloads as wl
@@ -36,7 +37,8 @@ def main() -> int:
         ext = dict(ext_o=np.zeros((n, w.num_q_heads, w.head_dim), np.float32),
                    ext_lse=np.zeros((n, w.num_q_heads), np.float32), ext_offsets=off)
     pools = 4 if args.workload == "cfg4" else 2
-    dw = DeviceWorkload(w, n_pool_copies=pools, mode="final" if len(w.calls) == 1 else "merge", **ext)
+    dw = DeviceWorkload(w, n_pool_copies=pools, mode="fused" if args.fused else ("final" if len(w.calls) == 1 else "merge"),
+                        **ext)
     n_wg, words = binding.omni_debug_decode_timeline_shape()
     stamps = torch.zeros(n_wg * words, dtype=torch.int64, device="cuda")
     dw.plan()
@@ -65,8 +67,8 @@ def main() -> int:
     def q(x, qs=(0, 10, 50, 90, 100)):
         return " ".join("%7.2f" % v for v in np.nanpercentile(x, qs))
 
-    print("%s: %d launches, %d workgroups (%d with work); events: stamping instance %.2f us, plain kernel %.2f us"
-          % (w.name, len(recs), n_wg, int(active[0].sum()), float(np.median(t_timed)), float(np.median(t_plain))))
+    print("%s%s: %d launches, %d workgroups (%d with work); events: stamping instance %.2f us, plain kernel %.2f us"
+          % (w.name, " (fused form)" if args.fused else "", len(recs), n_wg, int(active[0].sum()), float(np.median(t_timed)), float(np.median(t_plain))))
     print("  times in us after the launch's earliest workgroup start; percentiles over workgroups and launches")
     print("                                 min     p10     p50     p90     max")
     print("  workgroup start            %s" % q(start))
