@@ -108,6 +108,7 @@ def make_device_workload(name, cores, pools):
     # the masked merge does the rest; a single one-chunk call with nothing to merge writes all rows itself
     mode = "final" if len(w.calls) == 1 else "merge"
     dw = DeviceWorkload(w, n_pool_copies=max(1, pools), mode=mode, **ext)
+    dw.host_rows = ext                                  # (kept for the fused-form measurement of the hybrid batch)
     return w, dw, host_producer
 
 
@@ -205,6 +206,26 @@ def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
     }
     if host_producer is not None:
         rep["host_partial_producer"] = host_producer
+        # the hybrid batch also in the fused form: the attention launch folds the host-produced rows in and
+        # finishes every sequence itself, no merge launch (same inputs, list rebuilt every step)
+        from paper_2603_12831_amd.runner import DeviceWorkload
+        fdw = DeviceWorkload(w, n_pool_copies=max(1, pools), mode="fused", **dw.host_rows)
+
+        def fused_step(i):
+            fdw.plan()
+            fdw.run_attention(kernel=kernel, pool=i % pools, planned=True)
+
+        for i in range(max(warmup, 10)):
+            fused_step(i)
+        torch.cuda.synchronize()
+        f0 = time.perf_counter()
+        for i in range(steps):
+            fused_step(i)
+        torch.cuda.synchronize()
+        f_ms = (time.perf_counter() - f0) * 1e3 / steps
+        rep["fused_form"] = {"ms_per_step": f_ms, "value": kv_bytes / (f_ms * 1e-3) / 1e9, "unit": "GB/s",
+                             "pct_hbm_peak": 100.0 * kv_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "steps": steps}
+        del fdw
     return rep, w, dw
 
 

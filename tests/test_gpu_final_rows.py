@@ -221,6 +221,62 @@ def test_final_rows_with_sources_need_seq_final_and_partials():
     assert binding.omni_paged_decode_attn_raw(args, check=False) == binding.OMNI_ERR_NULL
 
 
+def hybrid_batch(seed, hq, hkv, pieces, dtype="bf16"):
+    """Sequences whose last tokens are resident and whose prefix comes as pieces[i] rows computed elsewhere
+    (0 = the whole context is resident)."""
+    rng = np.random.default_rng([seed, hq, hkv])
+    n = len(pieces)
+    lengths = rng.integers(200, 900, size=n)
+    tail = rng.integers(3, 150, size=n)
+    w = wl.make_generic(seed, lengths, hq, hkv, 128, dtype=dtype, pool_factor=1.3)
+    begin = np.where(np.array(pieces) > 0, lengths - tail, 0).astype(np.int32)
+    w.calls = [wl.DecodeCall(begin, lengths.astype(np.int32), 0, 1)]
+    ext = []
+    for i, k in enumerate(pieces):
+        cuts = [(int(begin[i]) * j) // k for j in range(k + 1)] if k else []
+        ext.append([(cuts[j], cuts[j + 1]) for j in range(k)])
+    w.ext_ranges = ext
+    return w
+
+
+@pytest.mark.parametrize("shape", [(8, 8), (8, 4), (6, 2), (16, 4), (16, 2), (32, 2)])
+def test_fused_form_hybrid_batches_of_every_head_group(shape):
+    """Rows from elsewhere through the LDS slots (up to four rows, up to four heads per kv head) and through
+    the merge routine (more rows, more heads), one to six rows per sequence and sequences without any, for
+    every group size up to 16 and both with the list built by the call and with a planned one."""
+    hq, hkv = shape
+    pieces = [1, 2, 3, 4, 0, 5, 6, 1, 4, 0, 2, 3, 4, 4, 1, 6, 2, 0, 3, 1]
+    w = hybrid_batch(77, hq, hkv, pieces)
+    ext = ext_partials_from_oracle(w)
+    exp = expected_full(w)
+    o_m, l_m, _ = run_mode(w, "merge", ext=ext)
+    check(o_m, l_m, exp[0], exp[1], TOL["bf16"], "two launches")
+    for kernel in (BENCH_FORM, PLANNED_LIST):
+        o_f, l_f, dw = run_mode(w, "fused", kernel, ext=ext, passes=3)
+        assert np.all(dw.seq_final.cpu().numpy() == 1)
+        check(o_f, l_f, exp[0], exp[1], TOL["bf16"], "fused hybrid, G = %d" % (hq // hkv))
+    # the tails cut into chunks: the last workgroup of a (sequence, kv head) merges chunks and rows
+    c = w.calls[0]
+    c.chunk_tokens, c.max_chunks = 32, int((int((c.ctx_end - c.ctx_begin).max()) + 31) // 32)
+    o_c, l_c, _ = run_mode(w, "fused", ext=ext, passes=2)
+    check(o_c, l_c, exp[0], exp[1], TOL["bf16"], "fused hybrid, chunked tails, G = %d" % (hq // hkv))
+
+
+def test_fused_form_dense_external_source():
+    """The external source given as a fixed number of rows per sequence instead of row offsets."""
+    w = hybrid_batch(78, 16, 4, [3] * 12)
+    ext = ext_partials_from_oracle(w)
+    exp = expected_full(w)
+    dw = DeviceWorkload(w, out_dtype="f32", ext_o=ext[0], ext_lse=ext[1], ext_offsets=ext[2], mode="fused")
+    dw.ext = (dw.ext[0], dw.ext[1], None, 3)
+    for _ in range(2):
+        dw.poison_outputs()
+        dw.run()
+    o, l = dw.results()
+    check(o, l, exp[0], exp[1], TOL["bf16"], "fused hybrid, dense source")
+    assert dw.abandoned_waves() == 0
+
+
 def test_fused_form_needs_the_persistent_kernel():
     w = mixed_batch(seed=75)
     dw = DeviceWorkload(w, out_dtype="f32", workspace=False, mode="fused")
