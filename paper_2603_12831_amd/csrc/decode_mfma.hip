@@ -1,4 +1,5 @@
-// Matrix-core decode attention for bf16 KV, head_dim 128, GQA ratio G <= 16.
+// Matrix-core decode attention for bf16 KV: head_dim 128 with GQA ratio G <= 16, and head_dim 64 with
+// G <= 4 as pairs of kv heads (further down).
 //
 // A work item is one (sequence, chunk, kv head): every KV byte of the chunk is
 // read exactly once and serves all G query heads that share the kv head (Eq. 1

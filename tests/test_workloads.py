@@ -86,3 +86,23 @@ def test_cfg4_recipe():
                 assert np.array_equal(w.dev_k_pool[dp], w.k_pool[w.block_table[i, lp]])
                 assert np.array_equal(w.dev_v_pool[dp], w.v_pool[w.block_table[i, lp]])
     assert w.dev_k_pool.shape[0] == int((w.dev_block_table >= 0).sum())
+
+
+def test_traffic_file_generator_reads_counter_tables(tmp_path):
+    """paper_2603_12831_amd.hbm_traffic: per-kernel means of a counter CSV; the fused instance of the persistent
+    kernel is a different kernel and is left out of the plain kernel's mean."""
+    from paper_2603_12831_amd import hbm_traffic
+    rows = [("void omni::(anonymous namespace)::copy_kernel(void*)", 524300.0),
+            ("void omni::(anonymous namespace)::copy_kernel(void*)", 524306.0),
+            ("void omni::(anonymous namespace)::decode_mfma_persistent_kernel<false, false, false>(omni::DecodeParams)", 100.0),
+            ("void omni::(anonymous namespace)::decode_mfma_persistent_kernel<false, false, false>(omni::DecodeParams)", 300.0),
+            ("void omni::(anonymous namespace)::decode_mfma_persistent_kernel<true, false, false>(omni::DecodeParams)", 9000.0),
+            ("void omni::(anonymous namespace)::merge_kernel<128>(omni::MergeParams)", 7.0)]
+    path = tmp_path / "p_counter_collection.csv"
+    with open(path, "w") as f:
+        f.write("Kernel_Name,Counter_Name,Counter_Value\n")
+        for k, v in rows:
+            f.write('"%s",FETCH_SIZE,%s\n' % (k, v))
+    mean, n = hbm_traffic.mean_per_kernel(str(path))
+    assert n == {"copy": 2, "decode": 2}
+    assert mean["copy"] == 524303.0 and mean["decode"] == 200.0
