@@ -18,6 +18,10 @@ measured after it with the same protocol and reported under "workloads".  One JS
                 kernel sources have changed since they were taken
   stream_read_GBps   a plain streaming read of the K pool on the same GPU; pct_of_stream_read: value against it
   list_reused   the same step when one work list serves many calls (the layers of a decoding iteration)
+  fused_form    (hybrid batch) the step when the attention launch folds the host-produced rows in and finishes
+                every sequence itself: no merge launch
+  host_partial_producer   (hybrid batch) the host-side producer of the rows computed elsewhere, against a
+                streaming read of the same host memory by the same threads
   cpu_baseline  the CPU fp64 oracle timed on this host on a bounded sample of the headline workload
 """
 from __future__ import annotations
@@ -204,6 +208,28 @@ def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
                      "kernel": binding.omni_decode_kernel_name(args0),
                      "algorithmic_bytes_per_launch": alg_bytes // n_calls},
     }
+    # The same step with the work list built once and reused (omni_decode_plan + workspace_planned), as the
+    # layers of one decoding iteration would share it: extra information, never `value`.
+    def rate(ms):
+        return {"ms_per_step": ms, "value": kv_bytes / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                "pct_hbm_peak": 100.0 * kv_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+    def time_steps(fn, n_warm):
+        for i in range(n_warm):
+            fn(i)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - c0) * 1e3 / steps
+
+    def step_planned(i):
+        dw.run_attention(kernel=kernel, pool=i % pools, planned=True)
+        dw.run_merge()
+
+    dw.plan()
+    rep["list_reused"] = rate(time_steps(step_planned, 5))
     if host_producer is not None:
         rep["host_partial_producer"] = host_producer
         # the hybrid batch also in the fused form: the attention launch folds the host-produced rows in and
@@ -215,16 +241,8 @@ def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
             fdw.plan()
             fdw.run_attention(kernel=kernel, pool=i % pools, planned=True)
 
-        for i in range(max(warmup, 10)):
-            fused_step(i)
-        torch.cuda.synchronize()
-        f0 = time.perf_counter()
-        for i in range(steps):
-            fused_step(i)
-        torch.cuda.synchronize()
-        f_ms = (time.perf_counter() - f0) * 1e3 / steps
-        rep["fused_form"] = {"ms_per_step": f_ms, "value": kv_bytes / (f_ms * 1e-3) / 1e9, "unit": "GB/s",
-                             "pct_hbm_peak": 100.0 * kv_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "steps": steps}
+        rep["fused_form"] = rate(time_steps(fused_step, max(warmup, 10)))
+        rep["fused_form"]["list_reused"] = rate(time_steps(lambda i: fdw.run_attention(kernel=kernel, pool=i % pools, planned=True), 5))
         del fdw
     return rep, w, dw
 
@@ -286,7 +304,7 @@ def main() -> int:
                    "pool_copies_rotated": pools, "final_rows": head["final_rows"]},
     }
     for k in ("pct_hbm_peak", "step_ms_median", "step_ms_min", "merged_tokens_per_s", "attention_kernel_ms",
-              "attention_kernel_ms_min", "roofline", "host_partial_producer"):
+              "attention_kernel_ms_min", "roofline", "host_partial_producer", "fused_form"):
         if k in head:
             out[k] = head[k]
 
@@ -300,22 +318,7 @@ def main() -> int:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
-    # The same step with the work list built once and reused (omni_decode_plan + workspace_planned), as the
-    # layers of one decoding iteration would share it: extra information, never `value`.
-    def step_planned(i):
-        dw.run_attention(kernel=args.kernel, pool=i % pools, planned=True)
-        dw.run_merge()
-    dw.plan()
-    for i in range(min(args.warmup, 5)):
-        step_planned(i)
-    torch.cuda.synchronize()
-    p0 = time.perf_counter()
-    for i in range(args.steps):
-        step_planned(i)
-    torch.cuda.synchronize()
-    planned_ms = (time.perf_counter() - p0) * 1e3 / args.steps
-    out["list_reused"] = {"ms_per_step": planned_ms, "value": kv_bytes / (planned_ms * 1e-3) / 1e9, "unit": "GB/s",
-                          "pct_hbm_peak": 100.0 * kv_bytes / (planned_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    out["list_reused"] = head["list_reused"]
     # the read rate of a plain streaming kernel over the same K pool (what this GPU's HBM gives a pure read)
     pool0 = dw.k_pools[0]
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
