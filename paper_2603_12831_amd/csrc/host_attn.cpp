@@ -19,6 +19,7 @@
 #include <cstdint>
 #include <cstring>
 #include <limits>
+#include <memory>
 #include <thread>
 #include <vector>
 
@@ -362,7 +363,10 @@ void produce(const HostParams& p, int n_threads, UnitFn unit_fn)
     first_unit.back() = units.size();
     const int G = p.group;
     const size_t stride = (size_t)G * (D + 2);                    // per unit: m[G], l[G], acc[G][D]
-    std::vector<float> partial(units.size() * stride);
+    // (not a std::vector: that would fill tens of megabytes with zeros on one thread before any work starts;
+    // every unit writes all of its slot)
+    std::unique_ptr<float[]> partial_mem(new float[units.size() * stride]);
+    float* const partial = partial_mem.get();
 
     auto run_parallel = [&](size_t count, auto&& body) {
         std::atomic<size_t> next{0};
@@ -378,7 +382,7 @@ void produce(const HostParams& p, int n_threads, UnitFn unit_fn)
 
     // longest units first would not matter (all are at most kSliceTokens); draw in order
     run_parallel(units.size(), [&](size_t i) {
-        float* res = partial.data() + i * stride;
+        float* res = partial + i * stride;
         unit_fn(p, units[i], res, res + G, res + 2 * G);
     });
 
@@ -400,7 +404,7 @@ void produce(const HostParams& p, int n_threads, UnitFn unit_fn)
             float o[D];
             for (int i = 0; i < D; ++i) o[i] = 0.f;
             for (size_t u = u0; u < u1; ++u) {
-                const float* res = partial.data() + u * stride;
+                const float* res = partial + u * stride;
                 if (res[g] == -std::numeric_limits<float>::infinity()) continue;
                 const float f = std::exp(res[g] - mm);
                 ll += f * res[G + g];
