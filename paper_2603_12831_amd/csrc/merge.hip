@@ -13,7 +13,7 @@
 namespace omni {
 namespace {
 
-template <int D>
+template <int D, int kBatch>
 __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
 {
     constexpr int kLanesPerRow = D / 4;
@@ -24,9 +24,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
     if (p.skip && p.skip[seq] != 0) return;                // the decode call already wrote this sequence's final row
 
-    // Rows are visited eight at a time so that eight independent loads are in flight per lane: the kernel
-    // is a handful of dependent memory round trips, not a bandwidth problem.
-    constexpr int kBatch = 8;
+    // Rows are visited kBatch at a time so that kBatch independent loads are in flight per lane: the kernel
+    // is a handful of dependent memory round trips, not a bandwidth problem.  The launcher picks kBatch by how
+    // many rows a sequence can have (fewer, larger turns for many rows; small turns, i.e. few registers and
+    // more resident workgroups, for two or three rows).
     float m = -INFINITY;
     for (int s = 0; s < p.n_srcs; ++s) {
         int r0, r1;
@@ -85,17 +86,33 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
 
 }  // namespace
 
+namespace {
+
+template <int kBatch>
+void launch_merge_batch(const MergeParams& p, long long rows, hipStream_t s)
+{
+    if (p.d == 64) {
+        unsigned grid = (unsigned)((rows + 15) / 16);
+        hipLaunchKernelGGL((merge_kernel<64, kBatch>), dim3(grid), dim3(256), 0, s, p);
+    } else {
+        unsigned grid = (unsigned)((rows + 7) / 8);
+        hipLaunchKernelGGL((merge_kernel<128, kBatch>), dim3(grid), dim3(256), 0, s, p);
+    }
+}
+
+}  // namespace
+
 hipError_t launch_merge(const MergeParams& p, hipStream_t s)
 {
     long long rows = (long long)p.batch * p.hq;
     if (rows == 0) return hipSuccess;
-    if (p.d == 64) {
-        unsigned grid = (unsigned)((rows + 15) / 16);
-        hipLaunchKernelGGL((merge_kernel<64>), dim3(grid), dim3(256), 0, s, p);
-    } else {
-        unsigned grid = (unsigned)((rows + 7) / 8);
-        hipLaunchKernelGGL((merge_kernel<128>), dim3(grid), dim3(256), 0, s, p);
-    }
+    // rows a sequence may have: what the dense sources say, two for a source with row offsets (measured:
+    // turns of 4 / 8 / 16 rows are best for the hybrid batch / 8-chunk rows / 32-chunk rows, each by 1-3 us)
+    long long hint = 0;
+    for (int i = 0; i < p.n_srcs; ++i) hint += p.src[i].row_offsets ? 2 : p.src[i].dense_rows_per_seq;
+    if (hint <= 4) launch_merge_batch<4>(p, rows, s);
+    else if (hint <= 12) launch_merge_batch<8>(p, rows, s);
+    else launch_merge_batch<16>(p, rows, s);
     return hipGetLastError();
 }
 
