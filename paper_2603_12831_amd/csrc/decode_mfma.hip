@@ -1391,6 +1391,41 @@ __device__ __forceinline__ void persistent_body(
     auto bring_ext = [&](int third, const Item& x, ExtRows e) {
         if (fused && e.rows > 0) issue_ext(p, x, e.first, e.rows, id.lane, ext_slot(third, x.ds == 1 ? id.wave : 0));
     };
+    // The workgroup's last ticket has nothing to stream behind it.  When its items are one per wave, each
+    // wave stores the rows of its own item instead of leaving the four to the writer wave one after the
+    // other: on batches of short items those four combines in a row are the end of the launch (measured on
+    // the hybrid batch: the writer finished 3.2 us after the streaming waves, 6.4 us in the fused form).
+    // Only rows that need nothing beyond the item's own state and its LDS slot go this way (`own_store`,
+    // decided from the ticket's staged words alike by the wave and by the writer); rows that are shared with
+    // other workgroups or go through the merge routine stay with the writer.
+    auto staged_item = [&](const int* si, int w, Item& x, int& mode, int& ext) {
+        x.seq = uniform(si[2 + 4 * w]);
+        x.chunk = uniform(si[3 + 4 * w]);
+        x.kvh = uniform(si[4 + 4 * w]);
+        mode = row_mode(p, chunk_live(x.chunk));
+        ext = 0;
+        if (fused && mode == kRowFinalFold) {
+            // rows from elsewhere: none (a plain final row), waiting in the item's LDS slot, or the merge routine's
+            ext = uniform(si[5 + 4 * w]);
+            if (ext == 0) mode = kRowFinal;
+        }
+    };
+    auto own_store = [&](int mode, int ext) { return !fused || mode == kRowFinal || (mode == kRowFinalFold && ext > 0); };
+    auto store_own_item = [&](int k, const int* si, const float* area) {
+        Item x;
+        int mode, ext;
+        staged_item(si, id.wave, x, mode, ext);
+        if (x.seq < 0 || !own_store(mode, ext)) return;
+        if (fused && mode == kRowFinalFold) {
+            const char* slot = ext_slot(k % 3, id.wave);
+            if (ext == 1) combine_fold_store<1>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
+            else if (ext == 2) combine_fold_store<2>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
+            else if (ext == 3) combine_fold_store<3>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
+            else combine_fold_store<4>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
+        } else {
+            combine_and_store<false, half>(p, x, area, p.group, id.lane, kWave, mode, nullptr, id.wave, id.wave + 1);
+        }
+    };
     unsigned tk = blockIdx.x;
     const bool writer = id.wave == kWaves;                 // the fifth wave
     if (writer) store_empty_share();
@@ -1422,16 +1457,12 @@ __device__ __forceinline__ void persistent_body(
             int n_jobs = 0;
             const int n_done = grouped ? kWaves : 1;
             for (int w = 0; w < n_done; ++w) {
-                done.seq = uniform(si[2 + 4 * w]);
-                done.chunk = uniform(si[3 + 4 * w]);
-                done.kvh = uniform(si[4 + 4 * w]);
+                int mode, ext;
+                staged_item(si, w, done, mode, ext);
                 if (done.seq < 0) continue;
-                int mode = row_mode(p, chunk_live(done.chunk));
+                if (last && grouped && own_store(mode, ext)) continue;      // the item's own wave stores these
                 shared |= mode == kRowShared;
                 if (fused && mode == kRowFinalFold) {
-                    // rows from elsewhere: none (a plain final row), waiting in the item's LDS slot, or the merge routine's
-                    const int ext = uniform(si[5 + 4 * w]);
-                    if (ext == 0) mode = kRowFinal;
                     if (ext > 0) {
                         const int w0 = grouped ? w : 0, w1 = grouped ? w + 1 : kWaves;
                         const char* slot = ext_slot(k % 3, w);
@@ -1478,7 +1509,7 @@ __device__ __forceinline__ void persistent_body(
         }
         if (timed && id.lane == 0) {
             OMNI_WAIT_VMCNT(0);
-            stamp[3] = wall_clock64();
+            atomicMax(&stamp[3], wall_clock64());          // (the streaming waves may store last, see below)
         }
         return;
     }
@@ -1620,7 +1651,17 @@ __device__ __forceinline__ void persistent_body(
             stamp[4] = (unsigned long long)(k + 1);
             stamp[5] = (unsigned long long)n_steps_wave0;
         }
-        if (!has_next) break;
+        if (!has_next) {
+            if (timed && threadIdx.x == 0) stamp[2] = wall_clock64();
+            if (uniform(sh_item[k & 1][1]) != 0) {         // (the word the writer wave goes by)
+                store_own_item(k, sh_item[k & 1], area);
+                if (timed && id.lane == 0) {
+                    OMNI_WAIT_VMCNT(0);
+                    atomicMax(&stamp[3], wall_clock64());
+                }
+            }
+            break;
+        }
         if (threadIdx.x == 0) lds_post(slot_next, kPending);   // every wave has read it; next used by ticket k+4
         read_q<half>(q_buffer(parity_next, nx), p.group, id.col, id.kg, qb);
         st.reset();
@@ -1628,7 +1669,6 @@ __device__ __forceinline__ void persistent_body(
         it_ext = nx_ext.rows;
     }
     OMNI_WAIT_VMCNT(0);                                    // no direct-to-LDS load may outlive the workgroup
-    if (timed && threadIdx.x == 0) stamp[2] = wall_clock64();
     if (gave_up && id.lane == 0) atomicAdd(ticket_counter + 5, 1u);
 }
 
