@@ -73,7 +73,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * kWave;
-constexpr int kPersistentThreads = kThreads + kWave;   // persistent form: four streaming waves and a writer wave
+// persistent form: four streaming waves and a writer wave - two in the fused form, where a writer's work on a
+// ticket of four short items (each item's rows folded with the rows from elsewhere: ~700 instructions an
+// item) otherwise takes longer than the streaming waves take for the ticket
+__host__ __device__ constexpr int persistent_writers(bool fused) { return fused ? 2 : 1; }
+__host__ __device__ constexpr int persistent_threads(bool fused) { return kThreads + persistent_writers(fused) * kWave; }
 constexpr int kD = 128;
 constexpr int kPageBytes = kBlockSize * kD * 2;        // one (page, kv head) tile of K or of V
 constexpr float kLog2e = 1.4426950408889634f;
@@ -1411,24 +1415,30 @@ __device__ __forceinline__ void persistent_body(
         }
     };
     auto own_store = [&](int mode, int ext) { return !fused || mode == kRowFinal || (mode == kRowFinalFold && ext > 0); };
+    // the rows of wave w's item under a one-item-per-wave ticket k (own_store(mode, ext) holds)
+    auto store_item = [&](int k, int w, const Item& x, int mode, int ext, const float* area) {
+        if (fused && mode == kRowFinalFold) {
+            const char* slot = ext_slot(k % 3, w);
+            // (the row count as a constant: the rows' loads and weights are straight-line code)
+            if (ext == 1) combine_fold_store<1>(p, x, area, id.lane, w, w + 1, slot);
+            else if (ext == 2) combine_fold_store<2>(p, x, area, id.lane, w, w + 1, slot);
+            else if (ext == 3) combine_fold_store<3>(p, x, area, id.lane, w, w + 1, slot);
+            else combine_fold_store<4>(p, x, area, id.lane, w, w + 1, slot);
+        } else {
+            combine_and_store<false, half>(p, x, area, p.group, id.lane, kWave, mode, nullptr, w, w + 1);
+        }
+    };
     auto store_own_item = [&](int k, const int* si, const float* area) {
         Item x;
         int mode, ext;
         staged_item(si, id.wave, x, mode, ext);
-        if (x.seq < 0 || !own_store(mode, ext)) return;
-        if (fused && mode == kRowFinalFold) {
-            const char* slot = ext_slot(k % 3, id.wave);
-            if (ext == 1) combine_fold_store<1>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
-            else if (ext == 2) combine_fold_store<2>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
-            else if (ext == 3) combine_fold_store<3>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
-            else combine_fold_store<4>(p, x, area, id.lane, id.wave, id.wave + 1, slot);
-        } else {
-            combine_and_store<false, half>(p, x, area, p.group, id.lane, kWave, mode, nullptr, id.wave, id.wave + 1);
-        }
+        if (x.seq >= 0 && own_store(mode, ext)) store_item(k, id.wave, x, mode, ext, area);
     };
     unsigned tk = blockIdx.x;
-    const bool writer = id.wave == kWaves;                 // the fifth wave
-    if (writer) store_empty_share();
+    const int writer_id = id.wave - kWaves;                // the waves behind the streaming ones
+    const bool writer = writer_id >= 0;
+    constexpr bool two_writers = persistent_writers(fused) == 2;
+    if (writer_id == 0) store_empty_share();
     if (tk >= n_tickets) return;
 
     // The writer wave does every global store of the workgroup: the rows of empty chunks now, then, ticket
@@ -1450,6 +1460,20 @@ __device__ __forceinline__ void persistent_body(
             const int* si = sh_item[k & 1];
             const bool last = si[0] != 0, grouped = si[1] != 0;
             const float* area = reinterpret_cast<const float*>(reinterpret_cast<const char*>(lds) + (k & 1) * comb_bytes);
+            // The second writer takes the odd items of a one-item-per-wave ticket, those that `own_store`
+            // says need nothing but their own state and LDS slot; everything else is the first writer's.
+            if (two_writers && writer_id == 1) {
+                if (grouped && !last) {
+                    for (int w = 1; w < kWaves; w += 2) {
+                        Item x;
+                        int mode, ext;
+                        staged_item(si, w, x, mode, ext);
+                        if (x.seq >= 0 && own_store(mode, ext)) store_item(k, w, x, mode, ext, area);
+                    }
+                }
+                if (last) break;
+                continue;
+            }
             // An item's rows are stored at once, unless they still have to be merged with rows from
             // elsewhere: those become jobs of the merge routine (at most one per item), run at the end.
             Item done;
@@ -1460,7 +1484,10 @@ __device__ __forceinline__ void persistent_body(
                 int mode, ext;
                 staged_item(si, w, done, mode, ext);
                 if (done.seq < 0) continue;
-                if (last && grouped && own_store(mode, ext)) continue;      // the item's own wave stores these
+                if (grouped && own_store(mode, ext)) {
+                    if (last) continue;                                    // the item's own wave stores these
+                    if (two_writers && (w & 1)) continue;                  // the second writer does
+                }
                 shared |= mode == kRowShared;
                 if (fused && mode == kRowFinalFold) {
                     if (ext > 0) {
@@ -1675,7 +1702,7 @@ __device__ __forceinline__ void persistent_body(
 // Header words 0 (ticket counter) and 3 (workgroups that have left) are the only mutable state of a work
 // list; the last workgroup to leave puts them back to zero, so the same list can serve the next call.
 template <bool fused, bool half, bool timed = false>
-__global__ __launch_bounds__(kPersistentThreads, 1) void decode_mfma_persistent_kernel(
+__global__ __launch_bounds__(persistent_threads(fused), 1) void decode_mfma_persistent_kernel(
     DecodeParams p, const int* __restrict__ block_table, unsigned* header,
     const unsigned* __restrict__ counts, const WorkEntry* __restrict__ entries, unsigned* arrivals)
 {
@@ -1788,7 +1815,7 @@ hipError_t device_facts(int& cus)
         int per_cu = 0;
         if (f.status == hipSuccess)
             f.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_persistent_kernel<true, false>,
-                                                                    kPersistentThreads, lds_p);
+                                                                    persistent_threads(true), lds_p);
         if (f.status == hipSuccess && (per_cu < 1 || f.cus < 1)) f.status = hipErrorLaunchOutOfResources;
         f.known = true;
     }
@@ -1844,7 +1871,7 @@ hipError_t launch_decode_mfma(const DecodeParams& given, void* workspace, bool p
                        : (p.fuse ? (p.stamps ? decode_mfma_persistent_kernel<true, false, true> : decode_mfma_persistent_kernel<true, false>)
                                  : (p.stamps ? decode_mfma_persistent_kernel<false, false, true>
                                              : decode_mfma_persistent_kernel<false, false>));
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kPersistentThreads), lds, s, p, p.block_table, header, header + 1,
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(persistent_threads(p.fuse != 0)), lds, s, p, p.block_table, header, header + 1,
                        entries, arrivals);
     return hipGetLastError();
 }
