@@ -275,6 +275,55 @@ def test_garbage_outside_the_range_is_never_used(kernel):
         run_and_check(w, kernel, expected=exp)
 
 
+def relocate_pools(dw, n_pages_big):
+    """The workload's pages moved to the far end of pools of n_pages_big pages (allocated on the device: the
+    rest holds zeros), the block table shifted with them."""
+    small = dw.k_pools[0].shape[0]
+    base = n_pages_big - small
+    for pools in (dw.k_pools, dw.v_pools):
+        big = torch.zeros((n_pages_big,) + tuple(pools[0].shape[1:]), dtype=pools[0].dtype, device=dw.device)
+        big[base:].copy_(pools[0])
+        pools[0] = big
+    dw.block_table = torch.where(dw.block_table >= 0, dw.block_table + base, dw.block_table)
+    dw._arg_cache.clear()
+    return base
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128)])
+def test_pages_beyond_4_gib_into_the_pools(kernel, dtype, d):
+    """Byte offsets of pages do not fit 32 bits: every page of the batch lies past 4 GiB in K and V pools of 4.5 GiB."""
+    hkv = 2
+    w = wl.make_generic(36, [700, 33, 2048, 1, 1500], 8, hkv, d, dtype=dtype, chunk_tokens=512, pool_factor=1.5)
+    exp = expected_full(w)
+    page_bytes = hkv * 16 * d * (2 if dtype == "bf16" else 4)
+    n_big = (9 << 29) // page_bytes
+    dw = DeviceWorkload(w, workspace=kernel[1])
+    base = relocate_pools(dw, n_big)
+    assert base * page_bytes > (1 << 32)
+    dw.poison_outputs()
+    dw.run(kernel=kernel[0])
+    got_o, got_l = dw.results()
+    assert dw.abandoned_waves() == 0
+    check(got_o, got_l, exp[0], exp[1], TOL[dtype], "pools of 4.5 GiB")
+    # the gather aid reads the same pages bit for bit
+    c = dw.calls[0]
+    args = binding.make_decode_args(dw.q, dw.k_pools[0], dw.v_pools[0], dw.block_table, c["begin"], c["end"],
+                                    sm_scale=w.sm_scale, chunk_tokens=c["chunk_tokens"], max_chunks=c["max_chunks"],
+                                    part_o=c["part_o"], part_lse=c["part_lse"])
+    L = int(w.ctx_len[2])
+    k_out = torch.zeros((L, hkv, d), dtype=dw.q.dtype, device=dw.device)
+    v_out = torch.zeros_like(k_out)
+    binding.omni_debug_gather_kv(args, 2, k_out, v_out)
+    torch.cuda.synchronize()
+    ek, ev = oracle.gather_kv(w.k_pool, w.v_pool, w.block_table, 2, 0, L)
+    view = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if dtype == "bf16" else (lambda t: t.cpu().numpy())
+    assert np.array_equal(view(k_out).view(np.uint8), ek.view(np.uint8))
+    assert np.array_equal(view(v_out).view(np.uint8), ev.view(np.uint8))
+    del dw
+    torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------------------
 # integer work: gather and index-revealing attention are bit-exact
 # ---------------------------------------------------------------------------

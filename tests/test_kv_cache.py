@@ -135,3 +135,54 @@ def test_gpu_append_then_decode_matches_oracle():
     exp_o, exp_l = oracle.paged_attn(w.q, w.k_pool, w.v_pool, w.block_table, None, w.ctx_len, w.sm_scale, "bf16",
                                      n_threads=8)
     assert np.max(np.abs(got_o - exp_o)) <= 2e-3 and np.max(np.abs(got_l - exp_l)) <= 2e-3
+
+
+@pytest.mark.gpu
+def test_gpu_append_and_pages_beyond_4_gib_into_the_pools():
+    """Pools of 4.5 GiB whose used pages all lie past 4 GiB: the appended token and the gathered / scattered
+    pages land bit for bit where the oracle puts them on the small pools."""
+    torch = pytest.importorskip("torch")
+    from paper_2603_12831_amd import binding
+    from paper_2603_12831_amd.runner import to_device
+    dtype, hkv, d = "bf16", 2, 128
+    rng = np.random.default_rng(11)
+    lengths = rng.integers(1, 300, size=9)
+    w = wl.make_generic(12, lengths + 1, 8, hkv, d, dtype=dtype, pool_factor=1.5)
+    dev = torch.device("cuda:0")
+    n_big = (9 << 29) // (hkv * 16 * d * 2)
+    base = n_big - w.num_blocks
+    assert base * hkv * 16 * d * 2 > (1 << 32)
+
+    def big(pool):
+        t = torch.zeros((n_big, hkv, 16, d), dtype=torch.bfloat16, device=dev)
+        t[base:].copy_(to_device(pool, dtype, dev))
+        return t
+    kp, vp = big(w.k_pool), big(w.v_pool)
+    bt_big = np.where(w.block_table >= 0, w.block_table + base, -1).astype(np.int32)
+    positions = lengths.astype(np.int32)
+    k_new = wl._normal((len(lengths), hkv, d), [12, 50], 1.0, dtype)
+    v_new = wl._normal((len(lengths), hkv, d), [12, 51], 1.0, dtype)
+    binding.omni_kv_append(kp, vp, torch.from_numpy(bt_big).to(dev), to_device(k_new, dtype, dev),
+                           to_device(v_new, dtype, dev), torch.from_numpy(positions).to(dev))
+    ek, ev = w.k_pool.copy(), w.v_pool.copy()
+    oracle.kv_append(ek, ev, w.block_table, k_new, v_new, positions)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(bits(kp[base:]), ek) and np.array_equal(bits(vp[base:]), ev)
+    assert not bits(kp[base - 64:base]).any()                        # nothing landed in front of them
+
+    ids = rng.permutation(w.num_blocks)[: w.num_blocks // 2].astype(np.int32)
+    ks = torch.full((len(ids), hkv, 16, d), 7.0, dtype=torch.bfloat16, device=dev)
+    vs = torch.full_like(ks, 7.0)
+    binding.omni_kv_gather_pages(kp, vp, torch.from_numpy(ids + base).to(dev), ks, vs)
+    gk, gv = oracle.kv_gather_pages(ek, ev, ids)
+    assert np.array_equal(bits(ks), gk) and np.array_equal(bits(vs), gv)
+    dest = rng.permutation(w.num_blocks)[: len(ids)].astype(np.int32)
+    kp[base:].zero_()
+    vp[base:].zero_()
+    binding.omni_kv_scatter_pages(kp, vp, torch.from_numpy(dest + base).to(dev), ks, vs)
+    ek2, ev2 = np.zeros_like(ek), np.zeros_like(ev)
+    oracle.kv_scatter_pages(ek2, ev2, dest, gk, gv)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(kp[base:]), ek2) and np.array_equal(bits(vp[base:]), ev2)
+    del kp, vp
+    torch.cuda.empty_cache()
