@@ -411,6 +411,17 @@ def test_matrix_core_group_sizes(kernel, shape):
     run_and_check(w, kernel)
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_one_context_of_131072_tokens(kernel):
+    """8 192 pages in one table row: as one range (4 096 steps of one item), as 128 chunks of 1 024 and as
+    2 048 chunks of 64 (the merge then folds 2 048 rows per head); a second, short sequence beside it."""
+    w = wl.make_generic(64, [131072, 77], 8, 2, 128, dtype="bf16", pool_factor=1.1, boost_frac=0.01, boost=8.0)
+    exp = expected_full(w)
+    for chunk, mc in [(0, 1), (1024, 128), (64, 2048)]:
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, mc
+        run_and_check(w, kernel, expected=exp)
+
+
 def test_work_list_with_many_sequences():
     """More sequences than the list kernel keeps in LDS (2048), most of them short, some empty."""
     rng = np.random.default_rng(62)
