@@ -277,6 +277,19 @@ def test_fused_form_dense_external_source():
     assert dw.abandoned_waves() == 0
 
 
+@pytest.mark.parametrize("mode", ["final", "fused"])
+def test_long_context_in_many_chunks(mode):
+    """One context of 131 072 tokens in 128 and in 2 048 chunks beside a one-chunk sequence: the in-launch
+    merge (fused) folds up to 2 048 rows per head, the other route leaves them to the masked merge."""
+    w = wl.make_generic(65, [131072, 50], 8, 2, 128, dtype="bf16", pool_factor=1.1, boost_frac=0.01, boost=8.0)
+    exp = expected_full(w)
+    for chunk, mc in [(1024, 128), (64, 2048)]:
+        w.calls[0].chunk_tokens, w.calls[0].max_chunks = chunk, mc
+        o, l, dw = run_mode(w, mode, passes=2)
+        check(o, l, exp[0], exp[1], TOL["bf16"], "%s, %d chunks" % (mode, mc))
+        assert np.array_equal(dw.seq_final.cpu().numpy(), np.array([mode == "fused", 1], dtype=np.int32))
+
+
 def test_fused_form_needs_the_persistent_kernel():
     w = mixed_batch(seed=75)
     dw = DeviceWorkload(w, out_dtype="f32", workspace=False, mode="fused")
