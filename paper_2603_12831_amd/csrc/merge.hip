@@ -13,6 +13,8 @@
 namespace omni {
 namespace {
 
+constexpr int kMaxSrcs = (int)(sizeof(MergeParams{}.src) / sizeof(omni_partial_src));   // sources of one call
+
 template <int D, int kBatch>
 __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
 {
@@ -22,6 +24,14 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     const int quad = threadIdx.x % kLanesPerRow;
     if (row >= (long long)p.batch * p.hq) return;
     const int seq = (int)(row / p.hq), head = (int)(row % p.hq);
+    // where the sequence's rows are in each source, requested together with the flag that may end the thread
+    // here (offsets read after the flag would be one more memory round trip in a kernel that is a handful of them)
+    int first[kMaxSrcs], last[kMaxSrcs];
+#pragma unroll
+    for (int s = 0; s < kMaxSrcs; ++s) {
+        first[s] = last[s] = 0;
+        if (s < p.n_srcs) src_rows(p.src[s], seq, first[s], last[s]);
+    }
     if (p.skip && p.skip[seq] != 0) return;                // the decode call already wrote this sequence's final row
 
     // Rows are visited kBatch at a time so that kBatch independent loads are in flight per lane: the kernel
@@ -29,9 +39,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     // many rows a sequence can have (fewer, larger turns for many rows; small turns, i.e. few registers and
     // more resident workgroups, for two or three rows).
     float m = -INFINITY;
-    for (int s = 0; s < p.n_srcs; ++s) {
-        int r0, r1;
-        src_rows(p.src[s], seq, r0, r1);
+#pragma unroll
+    for (int s = 0; s < kMaxSrcs; ++s) {
+        if (s >= p.n_srcs) break;
+        const int r0 = first[s], r1 = last[s];
         const float* lse = p.src[s].lse + head;
         for (int r = r0; r < r1; r += kBatch) {
             float l[kBatch];
@@ -44,9 +55,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeParams p)
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float wsum = 0.f;
     if (m != -INFINITY) {
-        for (int s = 0; s < p.n_srcs; ++s) {
-            int r0, r1;
-            src_rows(p.src[s], seq, r0, r1);
+#pragma unroll
+        for (int s = 0; s < kMaxSrcs; ++s) {
+            if (s >= p.n_srcs) break;
+            const int r0 = first[s], r1 = last[s];
             const float* lse = p.src[s].lse + head;
             const float* orow = p.src[s].o + (long long)head * D + quad * 4;
             for (int r = r0; r < r1; r += kBatch) {
