@@ -116,19 +116,28 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
         for (int i = 0; i < E; ++i) acc[g][i] = 0.f;
     }
 
+    // The pages of a turn's tokens are looked up one turn ahead (all of a turn's table entries in one go,
+    // requested behind the previous turn's K / V rows), so that a turn is one memory round trip - its rows -
+    // and not a chain of table entry, rows, table entry, rows ...
     const int* table = p.block_table + (long long)seq * p.max_blocks;
+    auto page_of_token = [&](int t) { return t < ce ? table[t >> 4] : -1; };
+    int pages[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) pages[u] = page_of_token(cb + grp + u * kGroups);
     for (int t0 = cb + grp; t0 < ce; t0 += kGroups * kUnroll) {
         float kx[kUnroll][E], vx[kUnroll][E];
         bool live[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int t = t0 + u * kGroups;
-            long long page = t < ce ? table[t >> 4] : -1;
+            const long long page = pages[u];
             live[u] = page >= 0 && page < p.num_blocks;          // absent page: its tokens do not exist
             const long long row = live[u] ? ((page * p.hkv + kvh) * kBlockSize + (t & 15)) * D + sub * E : 0;
             RowVec<T, E>::load(p.k_pool, row, kx[u]);
             RowVec<T, E>::load(p.v_pool, row, vx[u]);
         }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) pages[u] = page_of_token(t0 + (kUnroll + u) * kGroups);
         // a token that is not there: its weight will be zero, and its V must not reach the sums (0 * NaN)
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
