@@ -399,9 +399,12 @@ def test_deterministic_and_placement_independent(kernel):
 
 
 @pytest.mark.parametrize("kernel", KERNELS[1:])
-@pytest.mark.parametrize("shape", [(16, 1, 128), (8, 8, 128), (6, 3, 128), (24, 3, 128), (32, 2, 128)])
+@pytest.mark.parametrize("shape", [(16, 1, 128), (8, 8, 128), (6, 3, 128), (24, 3, 128), (32, 2, 128),
+                                   (56, 8, 128), (28, 4, 128), (16, 2, 128)])
 def test_matrix_core_group_sizes(kernel, shape):
-    """GQA ratios 16, 1, 2, 8 and 16 (the last needs the large LDS window) with ragged chunked contexts."""
+    """GQA ratios 16, 1, 2, 8 and 16 (the last needs the large LDS window) with ragged chunked contexts; then
+    the layer shapes of the paper's two models: 56 q / 8 kv heads (ratio 7) whole and halved for two GPUs,
+    64 q / 8 kv heads quartered for four."""
     hq, hkv, d = shape
     rng = np.random.default_rng(hq * 100 + hkv)
     lengths = rng.integers(1, 900, size=9)

@@ -13,7 +13,7 @@ from test_gpu_parity import TOL, expected_full, ext_partials_from_oracle
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = {128: [(8, 8), (8, 4), (6, 2), (16, 4), (16, 2), (32, 2), (32, 8), (12, 4), (5, 1)],
+SHAPES = {128: [(8, 8), (8, 4), (6, 2), (16, 4), (16, 2), (32, 2), (32, 8), (12, 4), (5, 1), (14, 2), (28, 4)],
           64: [(8, 8), (4, 2), (6, 2), (16, 4), (12, 4), (8, 1), (16, 2)]}
 FORMS = [(binding.OMNI_KERNEL_AUTO, False), (binding.OMNI_KERNEL_AUTO, True), (binding.OMNI_KERNEL_AUTO, 2),
          (binding.OMNI_KERNEL_VECTOR, False)]
