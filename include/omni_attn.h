@@ -417,7 +417,7 @@ omni_status omni_debug_host_stream_read(const void* src, size_t bytes, int32_t n
  * an instance of the persistent matrix-core kernel that also stamps a constant-rate clock (100 MHz, the same
  * for every workgroup) into `stamps` (device, n_words 64-bit words, zeroed by the caller): per workgroup w,
  * words_per_workgroup words from stamps[w * words_per_workgroup]: [0] start, [1] first query rows in LDS,
- * [2] streaming waves done, [3] the storing wave done, [4] tickets taken, [5] 32-token steps of wave 0,
+ * [2] streaming waves done, [3] the workgroup's last store done, [4] tickets taken, [5] 32-token steps of wave 0,
  * [8 + k] the workgroup's meeting after its k-th ticket (the first words_per_workgroup - 8 tickets).  A
  * workgroup without work stamps [0] only.  omni_debug_decode_timeline_shape tells how many workgroups a
  * launch on the current device has and how many words each writes.  Outputs are those of the plain call.

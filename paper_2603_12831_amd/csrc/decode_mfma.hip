@@ -1318,7 +1318,7 @@ __device__ __forceinline__ void persistent_body(
     const TicketSpace ts = make_ticket_space(min(counts[0], total), counts[5], (unsigned)p.hkv, gridDim.x);
     const unsigned n_tickets = ts.n_tickets;
     const float scale2 = p.sm_scale * kLog2e;
-    // [0] start, [1] first Q landed, [2] streaming waves done, [3] writer done, [4] tickets, [5] steps of wave 0,
+    // [0] start, [1] first Q landed, [2] streaming waves done, [3] last store done, [4] tickets, [5] steps of wave 0,
     // [8 + k] the workgroup's meeting after ticket k
     unsigned long long* const stamp = timed ? p.stamps + (size_t)blockIdx.x * kStampWords : nullptr;
     if (timed && threadIdx.x == 0) stamp[0] = wall_clock64();

@@ -74,7 +74,7 @@ def main() -> int:
     print("  workgroup start            %s" % q(start))
     print("  first query rows in LDS    %s" % q(first))
     print("  streaming waves done       %s" % q(stream_end))
-    print("  storing wave done          %s" % q(writer_end))
+    print("  last store done            %s" % q(writer_end))
     print("  launch end (last workgroup done), median over launches: %.2f us" % float(np.median(end)))
     idle = (end[:, None] - writer_end)
     print("  idle before the launch's end, per workgroup: mean %.2f us, p50 %.2f, p90 %.2f, max %.2f  "
