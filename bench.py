@@ -18,6 +18,8 @@ measured after it with the same protocol and reported under "workloads".  One JS
                 kernel sources have changed since they were taken
   stream_read_GBps   a plain streaming read of the K pool on the same GPU; pct_of_stream_read: value against it
   list_reused   the same step when one work list serves many calls (the layers of a decoding iteration)
+  unsplit       (chunked workloads; not with --only) context only: the same batch as one range per sequence,
+                i.e. without the split-KV the configuration prescribes (no partial rows, no merge launch)
   fused_form    (hybrid batch) the step when the attention launch folds the host-produced rows in and finishes
                 every sequence itself: no merge launch
   host_partial_producer   (hybrid batch) the host-side producer of the rows computed elsewhere, against a
@@ -131,7 +133,7 @@ def host_stream_reference(w, cores, host_kv, producer_seconds):
     return {"host_stream_read_GBps": rate, "frac_of_host_stream_read": (host_kv / producer_seconds / 1e9) / rate}
 
 
-def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
+def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0, unsplit=True):
     """Times one workload; returns (its report, the workload, the device buffers).  `min_seconds`: take more
     than `steps` steps (and warm-up steps) if that many would fill less than this much time - a timed region
     of a few milliseconds mostly measures its own two ends."""
@@ -230,6 +232,22 @@ def run_workload(name, steps, warmup, pools, kernel, cores, min_seconds=0.0):
 
     dw.plan()
     rep["list_reused"] = rate(time_steps(step_planned, 5))
+    if unsplit and len(w.calls) == 1 and w.calls[0].chunk_tokens > 0 and w.ext_ranges is None:
+        # Context, never `value`: the same batch handed over as one range per sequence (no split-KV, hence no
+        # partial rows and no merge launch; the kernel's tickets balance the load by themselves), list rebuilt.
+        import copy
+        from paper_2603_12831_amd.runner import DeviceWorkload
+        from paper_2603_12831_amd.workloads import DecodeCall
+        w1 = copy.copy(w)
+        w1.calls = [DecodeCall(w.calls[0].ctx_begin, w.calls[0].ctx_end, 0, 1)]
+        udw = DeviceWorkload(w1, mode="final", pools_from=dw)
+
+        def unsplit_step(i):
+            udw.plan()
+            udw.run_attention(kernel=kernel, pool=i % pools, planned=True)
+
+        rep["unsplit"] = rate(time_steps(unsplit_step, max(warmup, 10)))
+        del udw
     if host_producer is not None:
         rep["host_partial_producer"] = host_producer
         # the hybrid batch also in the fused form: the attention launch folds the host-produced rows in and
@@ -287,7 +305,9 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    head, w, dw = run_workload(args.workload, args.steps, args.warmup, pools_for(args.workload), args.kernel, cores)
+    # (--only is what the profiles run: every launch of the attention kernel is then one of the workload as configured)
+    head, w, dw = run_workload(args.workload, args.steps, args.warmup, pools_for(args.workload), args.kernel, cores,
+                               unsplit=not args.only)
     pools = pools_for(args.workload)
     kv_bytes = w.kv_bytes()
     out = {
@@ -319,6 +339,8 @@ def main() -> int:
         return a.elapsed_time(b) / n
 
     out["list_reused"] = head["list_reused"]
+    if "unsplit" in head:
+        out["unsplit"] = head["unsplit"]
     # the read rate of a plain streaming kernel over the same K pool (what this GPU's HBM gives a pure read)
     pool0 = dw.k_pools[0]
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")

@@ -25,13 +25,15 @@ class DeviceWorkload:
     def __init__(self, w: Workload, device="cuda:0", out_dtype: Optional[str] = None,
                  ext_o: Optional[np.ndarray] = None, ext_lse: Optional[np.ndarray] = None,
                  ext_offsets: Optional[np.ndarray] = None, n_pool_copies: int = 1, workspace: bool = True,
-                 mode: str = "merge"):
+                 mode: str = "merge", pools_from: Optional["DeviceWorkload"] = None):
         """mode: how the final rows come about.
         "merge"  every chunk writes a partial row, omni_merge_partials makes the final rows (a single
                  one-chunk call with nothing else to merge writes them itself);
         "final"  the decode call also writes the final rows of the sequences it can finish (one non-empty
                  chunk), the masked merge does the others;
-        "fused"  the decode call finishes every sequence (in-launch merge, external rows folded in)."""
+        "fused"  the decode call finishes every sequence (in-launch merge, external rows folded in).
+        pools_from: take q, the pool copies and the block table from that object instead of uploading them
+        again (the same batch with other ranges or another chunking)."""
         # workspace: False / 0 none (grid form), True / 1 a workspace whose list every call rebuilds,
         # 2 a workspace prepared once by omni_decode_plan and passed as planned to every call
         self.plan_first = workspace == 2 and workspace is not True
@@ -43,12 +45,16 @@ class DeviceWorkload:
         self.mode = mode
         self.w = w
         self.device = torch.device(device)
-        k_pool, v_pool, table = w.device_views()
-        self.q = to_device(w.q, w.dtype, self.device)
-        # several physical copies of the pools let a timing loop defeat cache residency
-        self.k_pools = [to_device(k_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
-        self.v_pools = [to_device(v_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
-        self.block_table = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).to(self.device)
+        if pools_from is not None:
+            self.q, self.k_pools, self.v_pools = pools_from.q, pools_from.k_pools, pools_from.v_pools
+            self.block_table = pools_from.block_table
+        else:
+            k_pool, v_pool, table = w.device_views()
+            self.q = to_device(w.q, w.dtype, self.device)
+            # several physical copies of the pools let a timing loop defeat cache residency
+            self.k_pools = [to_device(k_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
+            self.v_pools = [to_device(v_pool, w.dtype, self.device) for _ in range(n_pool_copies)]
+            self.block_table = torch.from_numpy(np.ascontiguousarray(table, dtype=np.int32)).to(self.device)
         B, Hq, D = w.batch, w.num_q_heads, w.head_dim
         self.calls = []
         for c in w.calls:
