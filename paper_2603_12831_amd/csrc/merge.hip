@@ -119,12 +119,13 @@ hipError_t launch_merge(const MergeParams& p, hipStream_t s)
     long long rows = (long long)p.batch * p.hq;
     if (rows == 0) return hipSuccess;
     // rows a sequence may have: what the dense sources say, two for a source with row offsets (measured:
-    // turns of 4 / 8 / 16 rows are best for the hybrid batch / 8-chunk rows / 32-chunk rows, each by 1-3 us)
+    // turns of 4 / 8 / 32 rows are best for the hybrid batch / 8-chunk rows / 32-chunk rows, each by 1-3 us)
     long long hint = 0;
     for (int i = 0; i < p.n_srcs; ++i) hint += p.src[i].row_offsets ? 2 : p.src[i].dense_rows_per_seq;
     if (hint <= 4) launch_merge_batch<4>(p, rows, s);
     else if (hint <= 12) launch_merge_batch<8>(p, rows, s);
-    else launch_merge_batch<16>(p, rows, s);
+    else if (hint <= 24) launch_merge_batch<16>(p, rows, s);
+    else launch_merge_batch<32>(p, rows, s);
     return hipGetLastError();
 }
 
