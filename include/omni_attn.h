@@ -133,12 +133,13 @@ typedef struct {
     int32_t out_dtype;
     float* out_lse;
     int32_t kernel;                /* omni_kernel                                             */
-    /* optional scratch for the matrix-core kernel's work list (device memory, caller-owned,
+    /* optional scratch for the call's work list (device memory, caller-owned,
      * at least omni_decode_workspace_bytes(batch, max_chunks, num_kv_heads) bytes, 16-byte aligned,
-     * contents need not survive between calls).  With it the kernel runs in its persistent form:
-     * non-empty chunks are listed longest-first and drawn by resident workgroups.  NULL selects the
-     * plain grid form.  Two calls that may overlap in time (different streams) need distinct
-     * workspaces.  The vector kernel ignores it.  The 32-bit word at byte 20 of a workspace that
+     * contents need not survive between calls).  With it the matrix-core kernel runs in its
+     * persistent form: non-empty chunks are listed longest-first and drawn by resident workgroups;
+     * the vector kernel launches one workgroup per list entry, in list order (longest first, empty
+     * chunk slots last).  NULL selects the plain grid form of either.  Two calls that may overlap
+     * in time (different streams) need distinct workspaces.  The 32-bit word at byte 20 of a workspace that
      * holds a list is a diagnostic: the list build zeroes it and a wave that gives a launch up
      * (its bounded wait for the next work item ran out, about a second) adds one; it stays zero
      * in every healthy run, and a non-zero value means rows of some launch since then are missing

@@ -94,16 +94,16 @@ omni_status decode_attn(const omni_decode_args* a, void* ws_given, uint64_t ws_b
     bool mfma = decode_mfma_supports(p, bf16);
     if (a->kernel == OMNI_KERNEL_MFMA && !mfma) return OMNI_ERR_UNSUPPORTED;
     if (a->kernel == OMNI_KERNEL_VECTOR) mfma = false;
-    void* ws = mfma ? ws_given : nullptr;
+    void* ws = ws_given;
     if (ws) {
         if (ws_bytes < decode_workspace_bytes(p.batch, p.max_chunks, p.hkv)) return OMNI_ERR_SHAPE;
         if (reinterpret_cast<uintptr_t>(ws) % 16 != 0) return OMNI_ERR_SHAPE;
     }
     // only the persistent form finishes every sequence, and only at head_dim 128
-    if (p.fuse && (!ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
+    if (p.fuse && (!mfma || !ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
     // the time-stamping instances are of the persistent form at head_dim 128
     if (p.stamps && (!mfma || !ws || p.d != 128)) return OMNI_ERR_UNSUPPORTED;
-    hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, s);
+    hipError_t e = mfma ? launch_decode_mfma(p, ws, planned, s) : launch_decode_vector(p, bf16, ws, planned, s);
     return e == hipSuccess ? OMNI_OK : OMNI_ERR_LAUNCH;
 }
 

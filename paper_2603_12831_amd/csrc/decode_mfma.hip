@@ -84,10 +84,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kSortBins = 256;
 
-// A non-empty token range [cb, ce) of one chunk; `chunk` carries the chunk index in its low 16 bits and the
-// number of non-empty chunks of the sequence in its high 16 bits (both are at most 65535).
-struct alignas(16) WorkEntry { int seq, chunk, cb, ce; };
-
 struct StepRegs {            // raw V registers of one 32-token step (pages A and B); K waits in LDS
     u32x4 va[4], vb[4];
 };
@@ -122,9 +118,6 @@ __device__ __forceinline__ WorkEntry load_invariant(const WorkEntry* ptr)
     return WorkEntry{v[0], v[1], v[2], v[3]};
 }
 
-__device__ __forceinline__ int pack_chunk(int chunk, int n_live) { return (int)((unsigned)chunk | ((unsigned)n_live << 16)); }
-__device__ __forceinline__ int chunk_index(int packed) { return packed & 0xffff; }
-__device__ __forceinline__ int chunk_live(int packed) { return (int)((unsigned)packed >> 16); }
 
 struct Pages { long long a, b; };                      // physical pages of a step, -1 = absent
 
@@ -1081,9 +1074,7 @@ __global__ __launch_bounds__(kThreads, 3) void decode_mfma_grid_kernel(DecodePar
 // ---------------------------------------------------------------------------------------------------
 // persistent form
 // ---------------------------------------------------------------------------------------------------
-// Workspace: 16 words of header (see decode_list_kernel), then batch * max_chunks entries, then one arrival
-// counter per (sequence, kv head).
-constexpr int kHeaderWords = 16;
+// (workspace layout: omni_internal.hpp)
 
 // Ranges of up to kShortTokens tokens ("short") are dealt out one per wave, four to a ticket; the sort keeps
 // them apart from the longer ones: bins 0 .. kLongBins-1 hold the longer ranges by scaled page count (bin 0

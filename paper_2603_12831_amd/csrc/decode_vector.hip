@@ -70,25 +70,48 @@ constexpr int kWaves = 4;
 constexpr int kGroups = kWaves * 4;            // 16-lane groups per workgroup
 constexpr int kUnroll = 4;                     // tokens a 16-lane group takes per turn
 
-// GMAX: compile-time bound of the heads per kv head the instance serves (registers are sized for it)
-template <typename T, int D, int GMAX>
-__global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodeParams p)
+// GMAX: compile-time bound of the heads per kv head the instance serves (registers are sized for it).
+// `listed`: the launch goes by a work list (`entries`: every (sequence, chunk) slot of the call, the non-empty
+// ranges longest first, then the empty ones): the grid walks the entries in list order, so the hardware, which
+// starts workgroups in grid order, deals the long ranges out first and the empty slots last - ragged batches
+// with many empty chunk slots otherwise ran at two thirds of the rate of uniform ones.  Without a list the
+// grid is (kv head, chunk slot, sequence) and every workgroup works its range out itself.
+template <typename T, int D, int GMAX, bool listed>
+__global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodeParams p, const WorkEntry* __restrict__ entries)
 {
     constexpr int E = D / 16;
     const int splits = (p.group + GMAX - 1) / GMAX;             // workgroups that share a kv head's heads
-    const int kvh = blockIdx.x / splits, chunk = blockIdx.y, seq = blockIdx.z;
-    const int head0 = kvh * p.group + (blockIdx.x % splits) * GMAX;
+    // (listed: a one-dimensional grid, the head blocks of an entry side by side as in the other form)
+    const int head_blocks = p.hkv * splits;
+    const int head_block = listed ? blockIdx.x % head_blocks : blockIdx.x;
+    const int kvh = head_block / splits;
+    const int head0 = kvh * p.group + (head_block % splits) * GMAX;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane & 15;                 // which E dims of the row
     const int grp = wave * 4 + (lane >> 4);    // which token of each 16-token turn
     const int G = min(GMAX, (kvh + 1) * p.group - head0);       // heads of this workgroup: head0 .. head0 + G - 1
 
-    int b, e, cb, ce;
-    seq_range(p, seq, b, e);
-    chunk_range(p, b, e, chunk, cb, ce);
+    int seq, chunk, cb, ce, n_parts;
+    if (listed) {
+        // (a list planned for these very ranges holds only values that pass unchanged; one reused against
+        // the contract is forced into bounds, so that wrong rows are the worst that can come of it)
+        const WorkEntry w = entries[blockIdx.x / head_blocks];
+        seq = min(max(w.seq, 0), p.batch - 1);
+        chunk = min(chunk_index(w.chunk), p.max_chunks - 1);
+        n_parts = chunk_live(w.chunk);
+        cb = max(w.cb, 0);
+        ce = min(w.ce, p.max_blocks * kBlockSize);
+    } else {
+        seq = blockIdx.z;
+        chunk = blockIdx.y;
+        int b, e;
+        seq_range(p, seq, b, e);
+        chunk_range(p, b, e, chunk, cb, ce);
+        n_parts = seq_parts(p, seq, b, e);
+    }
     // a sequence with at most one non-empty chunk (chunk 0) gets its final row from this kernel
-    const bool seq_direct = p.out_o != nullptr && seq_parts(p, seq, b, e) <= 1;
-    if (p.seq_final && blockIdx.x == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
+    const bool seq_direct = p.out_o != nullptr && n_parts <= 1;
+    if (p.seq_final && head_block == 0 && chunk == 0 && threadIdx.x == 0) p.seq_final[seq] = seq_direct ? 1 : 0;
 
     // Logits in the log2 domain and the hardware's exp2 / log2 (about one ulp), for both input types: the
     // library's expf / logf on natural logits gave fp32 inputs no smaller errors (seeded fp32 batches: worst
@@ -241,25 +264,42 @@ __global__ __launch_bounds__(kWaves * kWave) void decode_vector_kernel(DecodePar
     }
 }
 
-template <typename T, int D>
-hipError_t launch_for_group(const DecodeParams& p, hipStream_t s)
+template <typename T, int D, bool listed>
+hipError_t launch_for_group(const DecodeParams& p, const WorkEntry* entries, hipStream_t s)
 {
     const int per = p.group <= 1 ? 1 : (p.group <= 4 ? 4 : 8);            // heads a workgroup serves at most
     const int splits = (p.group + per - 1) / per;
-    dim3 grid(p.hkv * splits, p.max_chunks, p.batch), block(kWaves * kWave);
+    const long long listed_blocks = (long long)p.batch * p.max_chunks * p.hkv * splits;
+    if (listed && listed_blocks > 0x7fffffffLL) return hipErrorInvalidValue;       // (a list of that size: > 32 GB of entries)
+    const dim3 grid = listed ? dim3((unsigned)listed_blocks, 1, 1) : dim3(p.hkv * splits, p.max_chunks, p.batch);
+    const dim3 block(kWaves * kWave);
     const size_t lds = (size_t)(2 * kWaves * per + kWaves * per * D) * sizeof(float);
-    if (per == 1) hipLaunchKernelGGL((decode_vector_kernel<T, D, 1>), grid, block, lds, s, p);
-    else if (per == 4) hipLaunchKernelGGL((decode_vector_kernel<T, D, 4>), grid, block, lds, s, p);
-    else hipLaunchKernelGGL((decode_vector_kernel<T, D, 8>), grid, block, lds, s, p);
+    if (per == 1) hipLaunchKernelGGL((decode_vector_kernel<T, D, 1, listed>), grid, block, lds, s, p, entries);
+    else if (per == 4) hipLaunchKernelGGL((decode_vector_kernel<T, D, 4, listed>), grid, block, lds, s, p, entries);
+    else hipLaunchKernelGGL((decode_vector_kernel<T, D, 8, listed>), grid, block, lds, s, p, entries);
     return hipGetLastError();
+}
+
+template <bool listed>
+hipError_t launch_for_type(const DecodeParams& p, bool bf16, const WorkEntry* entries, hipStream_t s)
+{
+    if (bf16) return p.d == 64 ? launch_for_group<uint16_t, 64, listed>(p, entries, s)
+                               : launch_for_group<uint16_t, 128, listed>(p, entries, s);
+    return p.d == 64 ? launch_for_group<float, 64, listed>(p, entries, s) : launch_for_group<float, 128, listed>(p, entries, s);
 }
 
 }  // namespace
 
-hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s)
+// With a workspace the launch goes by the work list in it (built here unless `planned` says it is there).
+hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, void* workspace, bool planned, hipStream_t s)
 {
-    if (bf16) return p.d == 64 ? launch_for_group<uint16_t, 64>(p, s) : launch_for_group<uint16_t, 128>(p, s);
-    return p.d == 64 ? launch_for_group<float, 64>(p, s) : launch_for_group<float, 128>(p, s);
+    if (!workspace) return launch_for_type<false>(p, bf16, nullptr, s);
+    if (!planned) {
+        const hipError_t e = launch_decode_plan(p, workspace, s);
+        if (e != hipSuccess) return e;
+    }
+    const WorkEntry* entries = reinterpret_cast<const WorkEntry*>(static_cast<const unsigned*>(workspace) + kHeaderWords);
+    return launch_for_type<true>(p, bf16, entries, s);
 }
 
 }  // namespace omni

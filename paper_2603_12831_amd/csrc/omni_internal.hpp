@@ -131,8 +131,20 @@ __device__ __forceinline__ int seq_parts(const DecodeParams& p, int seq, int b, 
     return n;
 }
 
+// ---- the work list of a decode call (built by decode_list_kernel, see decode_mfma.hip) ---------------
+// Workspace: kHeaderWords words of header, then batch * max_chunks entries - the non-empty (sequence, chunk)
+// ranges longest first from the front, the empty ones from the back -, then one arrival counter per
+// (sequence, kv head).  An entry is a token range [cb, ce) of one chunk; `chunk` carries the chunk index in
+// its low 16 bits and the number of parts of the sequence (non-empty chunks, + 1 if other sources hold rows
+// for it) in its high 16 bits (both are at most 65535).
+constexpr int kHeaderWords = 16;
+struct alignas(16) WorkEntry { int seq, chunk, cb, ce; };
+__host__ __device__ __forceinline__ int pack_chunk(int chunk, int n_live) { return (int)((unsigned)chunk | ((unsigned)n_live << 16)); }
+__host__ __device__ __forceinline__ int chunk_index(int packed) { return packed & 0xffff; }
+__host__ __device__ __forceinline__ int chunk_live(int packed) { return (int)((unsigned)packed >> 16); }
+
 // ---- launchers (each defined beside its kernel) ---------------------------
-hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, hipStream_t s);
+hipError_t launch_decode_vector(const DecodeParams& p, bool bf16, void* workspace, bool planned, hipStream_t s);
 hipError_t launch_decode_mfma(const DecodeParams& p, void* workspace, bool planned, hipStream_t s);
 hipError_t launch_decode_plan(const DecodeParams& p, void* workspace, hipStream_t s);
 hipError_t decode_timeline_shape(int& n_workgroups, int& words_per_workgroup);

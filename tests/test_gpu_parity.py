@@ -23,10 +23,13 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-3}
 THREADS = 16
-# (kernel selector, give a workspace): the vector kernel, and both launch forms of the automatic choice
-# (which is the matrix-core kernel for bf16 / head_dim 128 and the vector kernel otherwise)
-# the last form is a workspace prepared once (omni_decode_plan) and passed as planned to every call
+# (kernel selector, give a workspace): the vector kernel in its grid form and launched by a work list, and
+# both launch forms of the automatic choice (which is the matrix-core kernel for bf16 at head_dim 128 and
+# some head_dim-64 shapes, the vector kernel otherwise); workspace 2 = a workspace prepared once
+# (omni_decode_plan) and passed as planned to every call
 KERNELS = [pytest.param((binding.OMNI_KERNEL_VECTOR, False), id="vector"),
+           pytest.param((binding.OMNI_KERNEL_VECTOR, True), id="vector-listed"),
+           pytest.param((binding.OMNI_KERNEL_VECTOR, 2), id="vector-listed-planned"),
            pytest.param((binding.OMNI_KERNEL_AUTO, False), id="auto-grid"),
            pytest.param((binding.OMNI_KERNEL_AUTO, True), id="auto-persistent"),
            pytest.param((binding.OMNI_KERNEL_AUTO, 2), id="auto-persistent-planned")]
@@ -398,7 +401,7 @@ def test_deterministic_and_placement_independent(kernel):
     assert np.array_equal(o1, o3) and np.array_equal(l1, l3)
 
 
-@pytest.mark.parametrize("kernel", KERNELS[1:])
+@pytest.mark.parametrize("kernel", KERNELS[3:])
 @pytest.mark.parametrize("shape", [(16, 1, 128), (8, 8, 128), (6, 3, 128), (24, 3, 128), (32, 2, 128),
                                    (56, 8, 128), (28, 4, 128), (16, 2, 128)])
 def test_matrix_core_group_sizes(kernel, shape):

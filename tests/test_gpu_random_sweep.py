@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 SHAPES = {128: [(8, 8), (8, 4), (6, 2), (16, 4), (16, 2), (32, 2), (32, 8), (12, 4), (5, 1), (14, 2), (28, 4)],
           64: [(8, 8), (4, 2), (6, 2), (16, 4), (12, 4), (8, 1), (16, 2)]}
 FORMS = [(binding.OMNI_KERNEL_AUTO, False), (binding.OMNI_KERNEL_AUTO, True), (binding.OMNI_KERNEL_AUTO, 2),
-         (binding.OMNI_KERNEL_VECTOR, False)]
+         (binding.OMNI_KERNEL_VECTOR, False), (binding.OMNI_KERNEL_VECTOR, True)]
 
 
 @pytest.fixture(scope="module", autouse=True)
