@@ -21,6 +21,21 @@ def test_header_symbols_are_exported():
         assert getattr(lib, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (no C++ in the signatures) with warnings on."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "omni_attn.h"\n'
+                   'int main(void) { omni_decode_args a; a.batch = 0; return (int)sizeof(a) == 0 || a.batch; }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_status_strings():
     assert binding.omni_status_string(0) == "OMNI_OK"
     for code in (-1, -2, -3, -4, -5):
